@@ -1,0 +1,159 @@
+"""Pins for the oracle's data movement and weighted sum: library gathers, closed forms, special
+cases and the accumulate error bound."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from definitions import random_topk
+
+
+def _rand_bf16(rng, shape):
+    return W.bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+
+@pytest.mark.parametrize("N,k,E,D,H", [(37, 2, 8, 4, 24), (64, 4, 16, 2, 40), (19, 8, 32, 8, 8), (50, 3, 6, 6, 16)])
+def test_dispatch_is_index_select(oracle, N, k, E, D, H):
+    rng = np.random.default_rng(N * H)
+    A = random_topk(rng, N, k, E)
+    x = _rand_bf16(rng, (N, H))
+    pl = oracle.plan(A, E, D)
+    send_buf, expert_buf = oracle.dispatch(pl, x)
+    # the rearrangement operator the paper measures (section 2.3) is index_select
+    xt = torch.from_numpy(x.astype(np.int32))
+    assert np.array_equal(expert_buf, torch.index_select(xt, 0, torch.from_numpy(pl.slot_token).long()).numpy())
+    assert np.array_equal(send_buf, torch.index_select(xt, 0, torch.from_numpy(pl.send_src).long()).numpy())
+    # row s of the expert tensor holds the row of the token whose expert id opens segment s
+    seg_expert = np.repeat(np.arange(E), pl.exp_count)
+    for s in range(pl.P):
+        t = pl.slot_token[s]
+        assert seg_expert[s] in A[t]
+        assert np.array_equal(expert_buf[s], x[t])
+
+
+def test_dispatch_aux_plane_follows_payload(oracle):
+    rng = np.random.default_rng(11)
+    A = random_topk(rng, 20, 4, 16)
+    x = rng.integers(0, 256, size=(20, 256), dtype=np.uint8)
+    sc = rng.standard_normal((20, 2)).astype(np.float32)
+    pl = oracle.plan(A, 16, 8)
+    send_buf, expert_buf, send_aux, expert_aux = oracle.dispatch(pl, x, sc)
+    assert np.array_equal(expert_buf, x[pl.slot_token]) and np.array_equal(expert_aux, sc[pl.slot_token])
+    assert np.array_equal(send_buf, x[pl.send_src]) and np.array_equal(send_aux, sc[pl.send_src])
+
+
+def test_dispatch_k1_is_row_permutation(oracle):
+    rng = np.random.default_rng(12)
+    A = random_topk(rng, 33, 1, 4)
+    x = _rand_bf16(rng, (33, 16))
+    pl = oracle.plan(A, 4, 2)
+    _, expert_buf = oracle.dispatch(pl, x)
+    assert np.array_equal(np.sort(expert_buf.view(np.uint16), axis=0), np.sort(x, axis=0))
+    assert np.array_equal(expert_buf[pl.pair_slot], x)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_combine_dyadic_weights_return_x_exactly(oracle, k):
+    # dispatch, identity experts, combine with w = 1/k: every product and partial sum is exact in
+    # single precision and the result is the bfloat16 input itself
+    rng = np.random.default_rng(20 + k)
+    N, E, D, H = 45, 16, 4, 32
+    A = random_topk(rng, N, k, E)
+    x = _rand_bf16(rng, (N, H))
+    pl = oracle.plan(A, E, D)
+    _, y = oracle.dispatch(pl, x)
+    w = np.full((N, k), 1.0 / k, dtype=np.float32)
+    o32, o16 = oracle.combine_f32(y, w, pl.pair_slot)
+    assert np.array_equal(o16, x)
+    assert np.array_equal(o32, W.bf16_bits_to_f32(x))
+    assert np.array_equal(oracle.combine_f64(y, w, pl.pair_slot), W.bf16_bits_to_f32(x).astype(np.float64))
+
+
+def test_combine_one_hot_selects_one_row(oracle):
+    rng = np.random.default_rng(30)
+    N, k, E, D, H = 31, 4, 8, 2, 16
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, D)
+    y = _rand_bf16(rng, (pl.P, H))
+    pick = rng.integers(0, k, size=N)
+    w = np.zeros((N, k), dtype=np.float32)
+    w[np.arange(N), pick] = 1.0
+    o32, o16 = oracle.combine_f32(y, w, pl.pair_slot)
+    want = y[pl.pair_slot.reshape(N, k)[np.arange(N), pick]]
+    assert np.array_equal(o16, want)
+    assert np.array_equal(oracle.combine_f64(y, w, pl.pair_slot), W.bf16_bits_to_f32(want).astype(np.float64))
+
+
+def test_combine_distinguishes_weight_order(oracle):
+    # a transposed or j-reversed weight lookup changes the result
+    N, k, E, D, H = 3, 2, 4, 2, 4
+    A = np.array([[0, 3], [2, 1], [1, 0]], dtype=np.int32)
+    pl = oracle.plan(A, E, D)
+    y = W.bf16_bits(np.arange(pl.P * H, dtype=np.float32).reshape(pl.P, H))
+    w = np.array([[0.25, 0.75], [0.5, 0.5], [1.0, 0.0]], dtype=np.float32)
+    yf = W.bf16_bits_to_f32(y).astype(np.float64)
+    want = np.zeros((N, H))
+    for t in range(N):
+        for j in range(k):
+            e = A[t, j]
+            # slot by definition: pairs with a smaller expert, then earlier pairs of the same expert
+            s = int(np.sum(A < e) + sum(1 for t2 in range(N) for j2 in range(k)
+                                        if A[t2, j2] == e and (t2, j2) < (t, j)))
+            want[t] += float(w[t, j]) * yf[s]
+    assert np.array_equal(oracle.combine_f64(y, w, pl.pair_slot), want)
+
+
+@pytest.mark.parametrize("ydt", ["bf16", "f32"])
+def test_combine_matches_fp64_library_sum_and_error_bound(oracle, ydt):
+    rng = np.random.default_rng(40)
+    N, k, E, D, H = 120, 8, 64, 8, 96
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, D)
+    if ydt == "bf16":
+        y = _rand_bf16(rng, (pl.P, H))
+        yf = W.bf16_bits_to_f32(y)
+    else:
+        y = rng.standard_normal((pl.P, H)).astype(np.float32)
+        yf = y
+    w = rng.random((N, k)).astype(np.float32)
+    w /= w.sum(1, keepdims=True)
+    # library cross-check: gather + einsum in double precision
+    yt = torch.from_numpy(yf.astype(np.float64))[torch.from_numpy(pl.pair_slot).long()].reshape(N, k, H)
+    want = torch.einsum("nk,nkh->nh", torch.from_numpy(w.astype(np.float64)), yt).numpy()
+    got64 = oracle.combine_f64(y, w, pl.pair_slot)
+    scale = oracle.combine_abs_f64(y, w, pl.pair_slot)
+    assert np.all(np.abs(got64 - want) <= 1e-15 * scale + 1e-300)
+    wantabs = torch.einsum("nk,nkh->nh", torch.from_numpy(w.astype(np.float64)), yt.abs()).numpy()
+    assert np.allclose(scale, wantabs, rtol=1e-14, atol=0)
+    # single-precision variant stays within k ulp(float32) of the scale: far inside the 1e-5 bar
+    o32, o16 = oracle.combine_f32(y, w, pl.pair_slot)
+    assert np.all(np.abs(o32.astype(np.float64) - got64) <= k * 2.0 ** -24 * scale)
+    # bfloat16 output is the nearest-even rounding of the float32 sum
+    assert np.array_equal(o16, W.bf16_bits(o32))
+    tb = torch.from_numpy(o32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(o16, tb)
+
+
+def test_combine_token_subset(oracle):
+    rng = np.random.default_rng(50)
+    N, k, E, D, H = 40, 4, 16, 4, 8
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, D)
+    y = _rand_bf16(rng, (pl.P, H))
+    w = rng.random((N, k)).astype(np.float32)
+    full = oracle.combine_f64(y, w, pl.pair_slot)
+    toks = np.array([39, 0, 7, 7, 21], dtype=np.int32)
+    assert np.array_equal(oracle.combine_f64(y, w, pl.pair_slot, tokens=toks), full[toks])
+    f32_full, b16_full = oracle.combine_f32(y, w, pl.pair_slot)
+    f32_sub, b16_sub = oracle.combine_f32(y, w, pl.pair_slot, tokens=toks)
+    assert np.array_equal(f32_sub, f32_full[toks]) and np.array_equal(b16_sub, b16_full[toks])
+
+
+def test_bf16_rounding_ties_to_even(oracle):
+    # 1 + 2^-8 is halfway between bfloat16 1.0 and 1 + 2^-7: ties go to the even mantissa (1.0);
+    # 1 + 3*2^-8 is halfway between 1 + 2^-7 and 1 + 2^-6: goes to 1 + 2^-6 (even)
+    y = np.array([[1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -1.0 - 2.0 ** -8]],
+                 dtype=np.float32)
+    w = np.ones((1, 1), dtype=np.float32)
+    _, o16 = oracle.combine_f32(y, w, np.zeros(1, dtype=np.int32))
+    assert o16.tolist() == [[0x3F80, 0x3F82, 0x3F81, 0xBF80]]
