@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused MoE shuffle hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic routing:
+    fusco_plan -> fusco_dispatch (x -> expert-major tensor) -> fusco_combine (identity experts)
+with every input already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config dsv3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def cpu_baseline(cfg, total_tokens, A, w, xb):
+    """The CPU oracle, as it stands, on the same workload: plan + two-hop dispatch + fp64 combine."""
+    import oracle
+    oracle.build()
+    t0 = time.perf_counter()
+    pl = oracle.plan(A, cfg.E, cfg.D)
+    _, eb = oracle.dispatch(pl, xb)
+    oracle.combine_f64(eb, w, pl.pair_slot)
+    dt = time.perf_counter() - t0
+    return {"value": cfg.N / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of %d tokens of the %s workload, one pass (plan + dispatch + fp64 combine), %.1f s"
+                      % (cfg.N, total_tokens, cfg.name, dt),
+            "host_cores_available": os.cpu_count()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="dsv3")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (expert-parallel devices are virtual partitions of "
+              "one GPU's buffers); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2512_22036_amd as fusco
+
+    fusco.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    torch.cuda.set_device(0)
+
+    cfg = W.get_config(args.config)
+    if cfg.payload != "bf16":
+        print("bench.py: only the bf16 configurations are timed here", file=sys.stderr)
+        return 2
+    A, w = W.make_routing(cfg)
+    xb = W.make_activations(cfg)
+
+    d_A = torch.from_numpy(A).cuda()
+    d_w = torch.from_numpy(w).cuda()
+    d_x = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+    L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+    d_expert = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+    d_out = torch.empty((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        fusco.fusco_plan(L, d_A)
+        fusco.fusco_dispatch(L, d_x, d_expert)
+        fusco.fusco_combine(L, d_expert, d_w, d_out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # timed region: K steps, with HIP events on the launch stream around every call
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record()
+        fusco.fusco_plan(L, d_A)
+        ev[i][1].record()
+        fusco.fusco_dispatch(L, d_x, d_expert)
+        ev[i][2].record()
+        fusco.fusco_combine(L, d_expert, d_w, d_out)
+        ev[i][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
+    plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
+    ms_per_step = wall * 1e3 / K
+    tokens_per_s = cfg.N * K / wall
+
+    # sanity: the identity-expert round trip gives sum_j w_j * x[t] = x[t] up to rounding
+    err = (d_out[:64].float() - d_x[:64].float()).abs().max().item()
+    if not err < 0.05:
+        print("bench.py: round trip is wrong (max error %g)" % err, file=sys.stderr)
+        return 1
+    status = int(L.array("status").item())
+
+    bytes_dispatch = (cfg.N + cfg.P) * cfg.row_bytes            # read N rows, write P rows
+    bytes_combine = (cfg.P + cfg.N) * cfg.H * 2                 # read P rows, write N rows
+    kernels = {
+        "dispatch": {"ms": float(disp_ms), "algorithmic_bytes": bytes_dispatch,
+                     "GBps": bytes_dispatch / (disp_ms * 1e-3) / 1e9},
+        "combine": {"ms": float(comb_ms), "algorithmic_bytes": bytes_combine,
+                    "GBps": bytes_combine / (comb_ms * 1e-3) / 1e9},
+        "plan": {"ms": float(plan_ms)},
+    }
+    dom = "dispatch" if disp_ms >= comb_ms else "combine"
+    achieved = kernels[dom]["GBps"]
+    both = (bytes_dispatch + bytes_combine) / ((disp_ms + comb_ms) * 1e-3) / 1e9
+
+    result = {
+        "metric": "dispatch+combine tokens/s and achieved HBM GB/s (% of peak), 1 MI355X",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: N=%d tokens, hidden=%d bf16, E=%d, top-%d, D=%d virtual devices; step = plan + "
+                               "dispatch + combine (identity experts)" % (cfg.name, cfg.N, cfg.H, cfg.E, cfg.k, cfg.D),
+                   "N": cfg.N, "hidden": cfg.H, "E": cfg.E, "k": cfg.k, "D": cfg.D, "seed": cfg.seed},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+        "kernels": kernels,
+        "dispatch_plus_combine": {"ms": float(disp_ms + comb_ms), "tokens_per_s": cfg.N / ((disp_ms + comb_ms) * 1e-3),
+                                  "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},
+        "invalid_ids": status,
+    }
+    if not args.no_cpu_baseline:
+        n = args.cpu_sample_tokens or cfg.N
+        sub = cfg.with_tokens(min(n, cfg.N))
+        result["cpu_baseline"] = cpu_baseline(sub, cfg.N, A[:sub.N], w[:sub.N], xb[:sub.N])
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

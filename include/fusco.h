@@ -1,0 +1,151 @@
+/*
+ * fusco.h - C boundary of the MI355X (gfx950) MoE token shuffle with the layout transformation
+ * fused into the data movement.
+ *
+ * The library turns the router's token-expert matrix into a two-level layout descriptor
+ * (fusco_plan), moves token rows straight to their final expert-major rows (fusco_dispatch) and
+ * brings expert outputs back into token order with the gate weights (fusco_combine).
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers into memory owned by the caller.  The library never
+ *     allocates, frees or keeps device memory, and never synchronises: each call only enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*; NULL is the default stream).
+ *   - Device pointers must be 16-byte aligned.  Buffers must not overlap, except that the y
+ *     argument of fusco_combine may be the expert buffer fusco_dispatch wrote.
+ *   - Return value: FUSCO_OK (0) when the work was enqueued, a negative FUSCO_ERR_* otherwise.
+ *     On an error nothing is launched.
+ *   - Expert-parallel devices are D virtual partitions of one GPU's buffers.  Expert e lives on
+ *     device e / (E / D) (contiguous placement; E must be a multiple of D).
+ *   - All row orders are deterministic: rows of one expert, and rows of one device's receive
+ *     tensor, are in ascending token order.
+ */
+#ifndef FUSCO_H
+#define FUSCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FUSCO_VERSION 100
+
+#define FUSCO_OK 0
+#define FUSCO_ERR_INVALID_ARG (-1) /* null pointer, size out of range, misaligned pointer or row size */
+#define FUSCO_ERR_WORKSPACE (-2)   /* caller-provided memory too small                               */
+#define FUSCO_ERR_UNSUPPORTED (-3) /* dtype or flag combination not implemented                       */
+#define FUSCO_ERR_HIP (-4)         /* the HIP runtime refused a launch                                */
+
+#define FUSCO_MAX_K 64   /* experts per token                    */
+#define FUSCO_MAX_E 1024 /* experts (and therefore devices)      */
+
+/* element types of fusco_combine */
+#define FUSCO_BF16 0
+#define FUSCO_F32 1
+
+/* flags of fusco_dispatch (0 means FUSCO_DISPATCH_EXPERT) */
+#define FUSCO_DISPATCH_EXPERT 1u /* write the expert-activation tensor (level 2 result)       */
+#define FUSCO_DISPATCH_WIRE 2u   /* write the deduplicated per-device receive tensors (level 1) */
+
+/*
+ * Layout descriptor: the two-level descriptor lists of the paper's Communication Planner
+ * (section 3.3, "Descriptor-level communication plan") for fixed-size segments.  A segment is one
+ * token row, so a segment descriptor (address, size) collapses to a row index.
+ *
+ * N tokens, k experts per token, E experts, D devices, P = N * k (token, expert) pairs.
+ * Pair index p = t * k + j.  "slot" = row in the expert-activation tensor [P rows], ordered by
+ * device, then expert, then token.  "send row" = row in the concatenated per-device receive
+ * tensors [U rows, U = send_off[D]], ordered by device, then token; a token has one send row per
+ * distinct destination device (first appearance of the device among its k entries).
+ * All arrays live in device memory carved by fusco_layout_bind.
+ */
+typedef struct fusco_layout {
+    int32_t N, k, E, D, P;
+    int32_t send_cap;        /* rows reserved for send_src and a wire buffer: N * min(k, D)          */
+    int32_t *exp_count;      /* [E]    rows per expert                                                */
+    int32_t *exp_off;        /* [E+1]  exclusive prefix sum of exp_count; exp_off[E] == P             */
+    int32_t *send_count;     /* [D]    send rows per device                                           */
+    int32_t *send_off;       /* [D+1]  exclusive prefix sum of send_count; send_off[D] == U           */
+    int32_t *pair_slot;      /* [P]    pair -> slot                 (level-2 receive descriptor)      */
+    int32_t *slot_pair;      /* [P]    slot -> pair                                                   */
+    int32_t *slot_token;     /* [P]    slot -> token                (source-token index)              */
+    int32_t *send_src;       /* [send_cap] send row -> token; rows >= U are not written (level-1 send) */
+    int32_t *pair_send_row;  /* [P]    pair -> send row of (t, device of its expert) (level-2 send)   */
+    int32_t *slot_send_row;  /* [P]    slot -> send row holding its payload                           */
+    uint8_t *pair_first;     /* [P]    1 iff the pair is the first appearance of its device in token t */
+    int32_t *status;         /* [1]    number of expert ids outside [0, E) seen by the last fusco_plan */
+} fusco_layout;
+
+/* Library version (FUSCO_VERSION of the build). */
+int fusco_version(void);
+
+/* Static text for a FUSCO_* return code. */
+const char *fusco_status_string(int status);
+
+/*
+ * Bytes of device memory the descriptor arrays need for these sizes (0 if the sizes are
+ * invalid: N < 0, k outside [1, FUSCO_MAX_K], E outside [1, FUSCO_MAX_E], D < 1, E % D != 0,
+ * or N * k >= 2^31).
+ */
+size_t fusco_layout_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
+
+/* Bytes of planner scratch (per-tile partial counts) for these sizes; 0 if the sizes are invalid. */
+size_t fusco_scratch_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
+
+/*
+ * Fill *L (host struct) with the sizes and with pointers carved out of the caller's device
+ * block d_mem of `bytes` bytes (256-byte aligned base).  Host-only: touches no device memory.
+ * Errors: FUSCO_ERR_INVALID_ARG (null, bad sizes, misaligned), FUSCO_ERR_WORKSPACE (too small).
+ */
+int fusco_layout_bind(fusco_layout *L, int32_t N, int32_t k, int32_t E, int32_t D, void *d_mem, size_t bytes);
+
+/*
+ * Planner (section 3.3): per-expert histogram, prefix-scan offsets, stable expert-major slot of
+ * every (t, e) pair, and removal of duplicate (token, device) sends with the resulting send rows.
+ * d_topk_idx: [N, k] int32 row-major, the token-expert matrix A (may be NULL when N == 0).  Ids outside [0, E) are counted
+ * in L->status, get pair_slot = pair_send_row = -1 and are skipped by dispatch and combine; the
+ * plan is then not a valid layout (slots at the end of the tensor stay unassigned).
+ * d_scratch: at least fusco_scratch_bytes() bytes, contents irrelevant before and after.
+ * Every descriptor array is fully rewritten (send_src only in rows < U).  N == 0 is allowed.
+ */
+int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size_t scratch_bytes, void *stream);
+
+/*
+ * Fused gather-pack (section 3.2, intra-node path: descriptor interpretation inlined into the
+ * copy, no intermediate pass): every token row is read once and written to each of its slots,
+ *     expert_buf[pair_slot[t*k+j]] = x[t]                          (FUSCO_DISPATCH_EXPERT)
+ *     send_buf[pair_send_row[t*k+j]] = x[t] where pair_first       (FUSCO_DISPATCH_WIRE)
+ * Rows are opaque bytes.  d_x: [N, row_bytes], row_bytes a positive multiple of 16.  An optional
+ * second plane (e.g. per-block scales of an fp8 payload) of aux_row_bytes (multiple of 16, or 0
+ * with NULL aux pointers) follows the same descriptors.  d_expert_buf: [P, row_bytes],
+ * d_expert_aux: [P, aux_row_bytes]; d_send_buf: [send_cap, row_bytes], d_send_aux likewise; rows
+ * >= U of the send buffers are not written.  Buffers of a plane that is not requested by `flags`
+ * may be NULL.
+ */
+int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
+                   size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
+                   void *d_send_aux, uint32_t flags, void *stream);
+
+/*
+ * Weighted combine (reverse path of the shuffle; "combined through a weighted summation",
+ * section 2.1):   out[t, :] = sum_{j=0..k-1} w[t, j] * y[pair_slot[t*k+j], :]
+ * accumulated in fp32 with one fused multiply-add per term in ascending j from +0, then rounded
+ * once (nearest even) when out_dtype is FUSCO_BF16.
+ * d_y: [P, H] of y_dtype, d_w: [N, k] fp32, d_out: [N, H] of out_dtype.  H * sizeof(y element)
+ * must be a multiple of 16.  `flags` must be 0.
+ */
+int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, void *d_out,
+                  int out_dtype, int32_t H, uint32_t flags, void *stream);
+
+/*
+ * Measurement aid: plain device copy of `bytes` bytes (multiple of 16) with the same 16-byte
+ * accesses the shuffle kernels use.  Used to calibrate hardware traffic counters and as the
+ * copy ceiling next to the shuffle's bandwidth.
+ */
+int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUSCO_H */

@@ -1,0 +1,14 @@
+"""MI355X-native MoE token shuffle with the layout transformation fused into the data movement.
+
+The work is done by hand-written HIP kernels in libfusco.so behind the C boundary declared in
+include/fusco.h; this package is a thin ctypes binding with the same names.  PyTorch supplies
+device memory and streams only.  There is no CPU or PyTorch fallback: without the built library
+every call raises.
+"""
+from .binding import (BF16, F32, DISPATCH_EXPERT, DISPATCH_WIRE, FuscoError, Layout, library_path,
+                      load_library, fusco_version, fusco_plan, fusco_dispatch, fusco_combine,
+                      fusco_probe_copy)
+
+__all__ = ["BF16", "F32", "DISPATCH_EXPERT", "DISPATCH_WIRE", "FuscoError", "Layout", "library_path",
+           "load_library", "fusco_version", "fusco_plan", "fusco_dispatch", "fusco_combine",
+           "fusco_probe_copy"]

@@ -1,0 +1,217 @@
+"""ctypes binding of libfusco.so: same names as the C boundary, argument marshalling only.
+
+Every step of the shuffle runs in the library's HIP kernels.  This module checks tensor shapes
+against the layout (the C side sees bare pointers), passes pointers and the current HIP stream,
+and turns negative return codes into FuscoError.  It never computes on the data and has no
+fallback path: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from types import SimpleNamespace
+from typing import Optional
+
+import torch
+
+BF16, F32 = 0, 1
+DISPATCH_EXPERT, DISPATCH_WIRE = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfusco.so")
+
+EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
+           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy")
+
+
+class FuscoError(RuntimeError):
+    pass
+
+
+class _CLayout(ctypes.Structure):
+    """Mirror of struct fusco_layout."""
+    _fields_ = [("N", ctypes.c_int32), ("k", ctypes.c_int32), ("E", ctypes.c_int32), ("D", ctypes.c_int32),
+                ("P", ctypes.c_int32), ("send_cap", ctypes.c_int32),
+                ("exp_count", ctypes.c_void_p), ("exp_off", ctypes.c_void_p),
+                ("send_count", ctypes.c_void_p), ("send_off", ctypes.c_void_p),
+                ("pair_slot", ctypes.c_void_p), ("slot_pair", ctypes.c_void_p),
+                ("slot_token", ctypes.c_void_p), ("send_src", ctypes.c_void_p),
+                ("pair_send_row", ctypes.c_void_p), ("slot_send_row", ctypes.c_void_p),
+                ("pair_first", ctypes.c_void_p), ("status", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libfusco.so (built by paper_2512_22036_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FuscoError("libfusco.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                         "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_uint32
+    lib.fusco_version.restype = ctypes.c_int
+    lib.fusco_version.argtypes = []
+    lib.fusco_status_string.restype = ctypes.c_char_p
+    lib.fusco_status_string.argtypes = [ctypes.c_int]
+    lib.fusco_layout_bytes.restype = sz
+    lib.fusco_layout_bytes.argtypes = [i32, i32, i32, i32]
+    lib.fusco_scratch_bytes.restype = sz
+    lib.fusco_scratch_bytes.argtypes = [i32, i32, i32, i32]
+    lib.fusco_layout_bind.restype = ctypes.c_int
+    lib.fusco_layout_bind.argtypes = [ctypes.POINTER(_CLayout), i32, i32, i32, i32, vp, sz]
+    lib.fusco_plan.restype = ctypes.c_int
+    lib.fusco_plan.argtypes = [ctypes.POINTER(_CLayout), vp, vp, sz, vp]
+    lib.fusco_dispatch.restype = ctypes.c_int
+    lib.fusco_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, sz, vp, sz, vp, vp, vp, vp, u32, vp]
+    lib.fusco_combine.restype = ctypes.c_int
+    lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
+    lib.fusco_probe_copy.restype = ctypes.c_int
+    lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise FuscoError("%s failed: %s (%d)" % (what, load_library().fusco_status_string(rc).decode(), rc))
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _rows(t: torch.Tensor, name: str, min_rows: int, row_bytes: Optional[int] = None) -> int:
+    if not t.is_cuda or t.dim() != 2 or not t.is_contiguous():
+        raise FuscoError("%s must be a contiguous 2-D device tensor" % name)
+    if t.shape[0] < min_rows:
+        raise FuscoError("%s has %d rows, needs %d" % (name, t.shape[0], min_rows))
+    rb = t.shape[1] * t.element_size()
+    if row_bytes is not None and rb != row_bytes:
+        raise FuscoError("%s rows are %d bytes, expected %d" % (name, rb, row_bytes))
+    return rb
+
+
+def fusco_version() -> int:
+    return load_library().fusco_version()
+
+
+_I32_FIELDS = {"exp_count": "E", "exp_off": "E+1", "send_count": "D", "send_off": "D+1", "pair_slot": "P",
+               "slot_pair": "P", "slot_token": "P", "send_src": "send_cap", "pair_send_row": "P",
+               "slot_send_row": "P", "status": "1"}
+
+
+class Layout:
+    """Device-resident layout descriptor: owns the device block the C struct points into and the
+    planner scratch.  Arrays are exposed as torch views of that block (no copies)."""
+
+    def __init__(self, N: int, k: int, E: int, D: int, device="cuda"):
+        lib = load_library()
+        nbytes = lib.fusco_layout_bytes(N, k, E, D)
+        if nbytes == 0:
+            raise FuscoError("invalid layout sizes N=%d k=%d E=%d D=%d" % (N, k, E, D))
+        self.mem = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.scratch = torch.empty(lib.fusco_scratch_bytes(N, k, E, D), dtype=torch.uint8, device=device)
+        self.c = _CLayout()
+        _check(lib.fusco_layout_bind(ctypes.byref(self.c), N, k, E, D, self.mem.data_ptr(), nbytes),
+               "fusco_layout_bind")
+        self.N, self.k, self.E, self.D = N, k, E, D
+        self.P, self.send_cap = int(self.c.P), int(self.c.send_cap)
+
+    def array(self, name: str) -> torch.Tensor:
+        """Torch view of one descriptor array (int32, or uint8 for pair_first)."""
+        sizes = {"E": self.E, "E+1": self.E + 1, "D": self.D, "D+1": self.D + 1, "P": self.P,
+                 "send_cap": self.send_cap, "1": 1}
+        off = getattr(self.c, name) - self.mem.data_ptr()
+        if name == "pair_first":
+            return self.mem[off:off + self.P]
+        n = sizes[_I32_FIELDS[name]]
+        return self.mem[off:off + 4 * n].view(torch.int32)
+
+    def to_host(self) -> SimpleNamespace:
+        """Synchronising copy of every array to numpy (send_src cut to its U valid rows)."""
+        out = {n: self.array(n).cpu().numpy() for n in list(_I32_FIELDS) + ["pair_first"]}
+        U = int(out["send_off"][self.D])
+        out["send_src"] = out["send_src"][:max(0, min(U, self.send_cap))]
+        return SimpleNamespace(N=self.N, k=self.k, E=self.E, D=self.D, P=self.P, U=U, **out)
+
+
+def fusco_plan(layout: Layout, topk_idx: torch.Tensor, stream=None) -> None:
+    if (not topk_idx.is_cuda or topk_idx.dtype != torch.int32 or not topk_idx.is_contiguous()
+            or tuple(topk_idx.shape) != (layout.N, layout.k)):
+        raise FuscoError("topk_idx must be a contiguous int32 device tensor of shape [N, k]")
+    _check(load_library().fusco_plan(ctypes.byref(layout.c), topk_idx.data_ptr(), layout.scratch.data_ptr(),
+                                     layout.scratch.numel(), _stream(stream)), "fusco_plan")
+
+
+def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.Tensor] = None,
+                   x_aux: Optional[torch.Tensor] = None, expert_aux: Optional[torch.Tensor] = None,
+                   send_buf: Optional[torch.Tensor] = None, send_aux: Optional[torch.Tensor] = None,
+                   flags: int = 0, stream=None) -> None:
+    rb = _rows(x, "x", layout.N)
+    ab = _rows(x_aux, "x_aux", layout.N) if x_aux is not None else 0
+    eff = flags or DISPATCH_EXPERT
+    if eff & DISPATCH_EXPERT:
+        if expert_buf is None:
+            raise FuscoError("expert_buf is required")
+        _rows(expert_buf, "expert_buf", layout.P, rb)
+        if ab:
+            if expert_aux is None:
+                raise FuscoError("expert_aux is required")
+            _rows(expert_aux, "expert_aux", layout.P, ab)
+    if eff & DISPATCH_WIRE:
+        if send_buf is None:
+            raise FuscoError("send_buf is required")
+        _rows(send_buf, "send_buf", layout.send_cap, rb)
+        if ab:
+            if send_aux is None:
+                raise FuscoError("send_aux is required")
+            _rows(send_aux, "send_aux", layout.send_cap, ab)
+    _check(load_library().fusco_dispatch(ctypes.byref(layout.c), x.data_ptr(), rb, _ptr(x_aux), ab,
+                                         _ptr(expert_buf), _ptr(expert_aux), _ptr(send_buf), _ptr(send_aux),
+                                         flags, _stream(stream)), "fusco_dispatch")
+
+
+def _dtype_code(t: torch.Tensor, name: str) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise FuscoError("%s must be bfloat16 or float32" % name)
+
+
+def fusco_combine(layout: Layout, y: torch.Tensor, w: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    _rows(y, "y", layout.P)
+    H = y.shape[1]
+    _rows(out, "out", layout.N)
+    if out.shape[1] != H:
+        raise FuscoError("out must have %d columns" % H)
+    if (not w.is_cuda or w.dtype != torch.float32 or not w.is_contiguous()
+            or tuple(w.shape) != (layout.N, layout.k)):
+        raise FuscoError("w must be a contiguous float32 device tensor of shape [N, k]")
+    _check(load_library().fusco_combine(ctypes.byref(layout.c), y.data_ptr(), _dtype_code(y, "y"), w.data_ptr(),
+                                        out.data_ptr(), _dtype_code(out, "out"), H, 0, _stream(stream)),
+           "fusco_combine")
+
+
+def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if not (dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()):
+        raise FuscoError("probe copy needs contiguous device tensors")
+    if dst.numel() * dst.element_size() < nbytes:
+        raise FuscoError("dst is smaller than src")
+    _check(load_library().fusco_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
+           "fusco_probe_copy")

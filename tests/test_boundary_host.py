@@ -1,0 +1,134 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every
+function the header declares, sizes and binds layouts, and rejects bad arguments before
+launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fusco.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2512_22036_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2512_22036_amd.build import build_library
+        build_library()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(fusco_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    from paper_2512_22036_amd import binding
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_status_strings(lib):
+    assert lib.fusco_version() == 100
+    assert lib.fusco_status_string(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert len(lib.fusco_status_string(code)) > 0
+
+
+def test_layout_sizes(lib):
+    assert lib.fusco_layout_bytes(8192, 8, 256, 8) >= 4 * (6 * 65536 + 2 * 257 + 2 * 9) + 65536
+    assert lib.fusco_layout_bytes(0, 8, 256, 8) > 0
+    assert lib.fusco_scratch_bytes(8192, 8, 256, 8) >= 32 * (256 + 8 + 1) * 4
+    bad = [(-1, 8, 256, 8), (16, 0, 256, 8), (16, 65, 256, 8), (16, 8, 0, 8), (16, 8, 2048, 8),
+           (16, 8, 256, 0), (16, 8, 256, 3), (16, 8, 8, 16), (1 << 30, 8, 256, 8)]
+    for args in bad:
+        assert lib.fusco_layout_bytes(*args) == 0, args
+        assert lib.fusco_scratch_bytes(*args) == 0, args
+
+
+def test_layout_bind_carves_disjoint_aligned_arrays(lib):
+    from paper_2512_22036_amd.binding import _CLayout
+    N, k, E, D = 100, 4, 16, 8
+    nbytes = lib.fusco_layout_bytes(N, k, E, D)
+    base = 0x10000000   # never dereferenced: bind is host-only pointer arithmetic
+    L = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, D, base, nbytes) == 0
+    assert (L.N, L.k, L.E, L.D, L.P, L.send_cap) == (N, k, E, D, N * k, N * min(k, D))
+    sizes = dict(exp_count=4 * E, exp_off=4 * (E + 1), send_count=4 * D, send_off=4 * (D + 1), pair_slot=4 * N * k,
+                 slot_pair=4 * N * k, slot_token=4 * N * k, send_src=4 * L.send_cap, pair_send_row=4 * N * k,
+                 slot_send_row=4 * N * k, pair_first=N * k, status=4)
+    spans = sorted((getattr(L, n), getattr(L, n) + s) for n, s in sizes.items())
+    assert spans[0][0] >= base and spans[-1][1] <= base + nbytes
+    for (a0, a1), (b0, _) in zip(spans, spans[1:]):
+        assert a1 <= b0
+    assert all(a0 % 256 == 0 for a0, _ in spans)
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, D, base, nbytes - 1) == -2
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, D, base + 16, nbytes) == -1
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, D, None, nbytes) == -1
+    assert lib.fusco_layout_bind(None, N, k, E, D, base, nbytes) == -1
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, 5, base, nbytes) == -1
+
+
+def test_entry_points_reject_bad_arguments_without_launching(lib):
+    from paper_2512_22036_amd.binding import _CLayout
+    N, k, E, D = 64, 2, 8, 4
+    nbytes = lib.fusco_layout_bytes(N, k, E, D)
+    base, buf = 0x10000000, 0x20000000
+    L = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(L), N, k, E, D, base, nbytes) == 0
+    scratch = lib.fusco_scratch_bytes(N, k, E, D)
+    # plan
+    assert lib.fusco_plan(ctypes.byref(L), None, buf, scratch, None) == -1
+    assert lib.fusco_plan(ctypes.byref(L), buf, None, scratch, None) == -1
+    assert lib.fusco_plan(ctypes.byref(L), buf, buf, scratch - 1, None) == -2
+    assert lib.fusco_plan(None, buf, buf, scratch, None) == -1
+    empty = _CLayout()
+    assert lib.fusco_plan(ctypes.byref(empty), buf, buf, scratch, None) == -1
+    # dispatch
+    d = lambda *a: lib.fusco_dispatch(ctypes.byref(L), *a)
+    assert d(None, 64, None, 0, buf, None, None, None, 0, None) == -1            # no x
+    assert d(buf, 0, None, 0, buf, None, None, None, 0, None) == -1              # empty rows
+    assert d(buf, 40, None, 0, buf, None, None, None, 0, None) == -1             # not a multiple of 16
+    assert d(buf, 64, None, 8, buf, None, None, None, 0, None) == -1             # aux not a multiple of 16
+    assert d(buf, 64, None, 16, buf, buf, None, None, 0, None) == -1             # aux plane without source
+    assert d(buf, 64, buf, 16, buf, None, None, None, 0, None) == -1             # aux plane without target
+    assert d(buf, 64, None, 0, None, None, None, None, 0, None) == -1            # no expert buffer
+    assert d(buf, 64, None, 0, buf, None, None, None, 2, None) == -1             # wire without send buffer
+    assert d(buf + 4, 64, None, 0, buf, None, None, None, 0, None) == -1         # misaligned
+    assert d(buf, 64, None, 0, buf, None, None, None, 8, None) == -3             # unknown flag
+    assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
+    # combine
+    c = lambda *a: lib.fusco_combine(ctypes.byref(L), *a)
+    assert c(None, 0, buf, buf, 0, 64, 0, None) == -1
+    assert c(buf, 0, None, buf, 0, 64, 0, None) == -1
+    assert c(buf, 0, buf, None, 0, 64, 0, None) == -1
+    assert c(buf, 0, buf, buf, 0, 0, 0, None) == -1
+    assert c(buf, 0, buf, buf, 0, 12, 0, None) == -1          # 24-byte rows
+    assert c(buf, 1, buf, buf, 1, 6, 0, None) == -1
+    assert c(buf, 2, buf, buf, 0, 64, 0, None) == -3          # unknown dtype
+    assert c(buf, 0, buf, buf, 7, 64, 0, None) == -3
+    assert c(buf, 0, buf, buf, 0, 64, 1, None) == -3          # flags must be 0
+    assert c(buf + 8, 0, buf, buf, 0, 64, 0, None) == -1
+    # probe copy
+    assert lib.fusco_probe_copy(None, buf, 64, None) == -1
+    assert lib.fusco_probe_copy(buf, buf + 4, 64, None) == -1
+    assert lib.fusco_probe_copy(buf, buf + 4096, 24, None) == -1
+    assert lib.fusco_probe_copy(buf, buf + 4096, 0, None) == 0
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2512_22036_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "fusco_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2512_22036_amd" not in text and "libfusco.so" not in text, f

@@ -1,0 +1,323 @@
+"""Parity of the HIP path against the CPU oracle, element by element, through the C boundary.
+
+Integer descriptors and moved bytes must be bit-exact.  The weighted sum must be (i) bit-exact
+against the oracle's single-precision fused-multiply-add sum in j order (the precision the method
+is specified in, both for float32 and bfloat16 outputs) and (ii) within 1e-5 * sum_j |w_j y_j| of
+the oracle's double-precision sum.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from definitions import PLAN_FIELDS, check_plan_invariants, random_topk
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def fusco():
+    import paper_2512_22036_amd as f
+    f.load_library()
+    assert torch.cuda.is_available()
+    return f
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.view(dtype) if dtype is not None else t
+
+
+def bf16_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bits_host(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def gpu_plan(fusco, A, E, D):
+    N, k = A.shape
+    L = fusco.Layout(N, k, E, D)
+    L.mem.fill_(0x7B)   # stale contents must not leak into the result
+    fusco.fusco_plan(L, dev(A.astype(np.int32)).reshape(N, k))
+    torch.cuda.synchronize()
+    return L, L.to_host()
+
+
+def assert_plan_equal(got, want):
+    assert int(got.status[0]) == 0
+    for f in PLAN_FIELDS:
+        assert np.array_equal(getattr(got, f), getattr(want, f)), f
+
+
+PLAN_SHAPES = [
+    # N, k, E, D, distinct experts per token
+    (1, 1, 1, 1, True), (1, 8, 256, 8, True), (5, 2, 4, 2, True), (64, 2, 16, 4, True),
+    (256, 8, 256, 8, True),        # exactly one tile
+    (257, 8, 256, 8, True),        # one tile and one token
+    (1000, 8, 256, 8, True),       # several tiles, ragged tail
+    (4096, 2, 16, 4, True), (3000, 8, 128, 16, True), (777, 6, 96, 12, True),
+    (300, 64, 1024, 64, True),     # largest k and E
+    (500, 3, 1024, 1024, True),    # one expert per device
+    (900, 4, 64, 1, True),         # single device
+    (1300, 5, 10, 5, False),       # repeated experts inside a token
+    (2100, 7, 7, 7, False), (129, 33, 66, 2, True),
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,distinct", PLAN_SHAPES)
+def test_plan_matches_oracle(fusco, oracle, N, k, E, D, distinct):
+    A = random_topk(np.random.default_rng(N * 31 + k), N, k, E, distinct)
+    L, got = gpu_plan(fusco, A, E, D)
+    want = oracle.plan(A, E, D)
+    assert_plan_equal(got, want)
+    assert got.U == want.U
+
+
+def test_plan_empty_input(fusco, oracle):
+    L, got = gpu_plan(fusco, np.zeros((0, 4), dtype=np.int32), 8, 2)
+    assert got.exp_off.tolist() == [0] * 9 and got.send_off.tolist() == [0] * 3
+    assert got.exp_count.tolist() == [0] * 8 and got.send_count.tolist() == [0] * 2 and int(got.status[0]) == 0
+
+
+def test_plan_skewed_all_to_one_expert(fusco, oracle):
+    A = np.zeros((5000, 1), dtype=np.int32) + 3
+    L, got = gpu_plan(fusco, A, 8, 4)
+    assert_plan_equal(got, oracle.plan(A, 8, 4))
+
+
+@pytest.mark.parametrize("name,n", [("tiny", 4096), ("dsv3", 8192), ("qwen3", 16384), ("skewed", 32768),
+                                    ("decode_fp8", 128)])
+def test_plan_on_full_configs(fusco, oracle, name, n):
+    cfg = W.get_config(name).with_tokens(n)
+    A, _ = W.make_routing(cfg)
+    L, got = gpu_plan(fusco, A, cfg.E, cfg.D)
+    want = oracle.plan(A, cfg.E, cfg.D)
+    assert_plan_equal(got, want)
+    check_plan_invariants(got, A)
+
+
+def test_plan_is_deterministic(fusco):
+    cfg = W.get_config("dsv3").with_tokens(3000)
+    A, _ = W.make_routing(cfg)
+    L, first = gpu_plan(fusco, A, cfg.E, cfg.D)
+    ref = L.mem.clone()
+    At = dev(A)
+    for _ in range(20):
+        fusco.fusco_plan(L, At)
+        torch.cuda.synchronize()
+        assert torch.equal(L.mem, ref)
+
+
+def test_plan_counts_invalid_ids(fusco, oracle):
+    rng = np.random.default_rng(77)
+    N, k, E, D = 700, 4, 32, 4
+    A = random_topk(rng, N, k, E)
+    bad = rng.choice(N * k, size=9, replace=False)
+    Ab = A.copy().reshape(-1)
+    Ab[bad[:5]] = E + 3
+    Ab[bad[5:]] = -2
+    Ab = Ab.reshape(N, k)
+    L, got = gpu_plan(fusco, Ab, E, D)
+    assert int(got.status[0]) == 9
+    assert np.all(got.pair_slot[bad] == -1) and np.all(got.pair_send_row[bad] == -1)
+    assert np.all(got.pair_first[bad] == 0)
+    ok = np.ones(N * k, dtype=bool)
+    ok[bad] = False
+    assert int(got.exp_count.sum()) == N * k - 9
+    # valid pairs still form a stable expert-major order among themselves
+    order = np.argsort(Ab.reshape(-1)[ok], kind="stable")
+    assert np.array_equal(got.slot_pair[:N * k - 9], np.flatnonzero(ok)[order])
+    # the movers skip invalid pairs instead of faulting
+    x = bf16_dev(W.bf16_bits(rng.standard_normal((N, 64)).astype(np.float32)))
+    eb = torch.zeros((N * k, 64), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_dispatch(L, x, eb)
+    out = torch.empty((N, 64), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_combine(L, eb, torch.full((N, k), 0.25, device="cuda"), out)
+    torch.cuda.synchronize()
+    # and a later valid plan on the same layout clears the status word
+    fusco.fusco_plan(L, dev(A))
+    torch.cuda.synchronize()
+    assert_plan_equal(L.to_host(), oracle.plan(A, E, D))
+
+
+DISPATCH_SHAPES = [
+    # N, k, E, D, row_bytes
+    (33, 2, 8, 4, 16), (100, 4, 16, 4, 48), (257, 8, 64, 8, 2048), (300, 8, 256, 8, 14336),
+    (513, 2, 16, 4, 16 * 37), (64, 3, 6, 3, 16 * 129), (40, 8, 32, 32, 16 * 1025), (1, 1, 1, 1, 4096),
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,row_bytes", DISPATCH_SHAPES)
+@pytest.mark.parametrize("flags", [0, 2, 3])
+def test_dispatch_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, flags):
+    rng = np.random.default_rng(N + row_bytes)
+    A = random_topk(rng, N, k, E)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    want = oracle.plan(A, E, D)
+    send_want, expert_want = oracle.dispatch(want, x)
+    L, got = gpu_plan(fusco, A, E, D)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    sb = torch.full((L.send_cap, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_dispatch(L, dev(x), eb if flags != 2 else None, send_buf=sb if flags & 2 else None, flags=flags)
+    torch.cuda.synchronize()
+    if flags != 2:
+        assert np.array_equal(eb.cpu().numpy(), expert_want)
+    else:
+        assert bool((eb == 0xEE).all())
+    if flags & 2:
+        assert np.array_equal(sb[:want.U].cpu().numpy(), send_want)
+        assert bool((sb[want.U:] == 0xEE).all())       # rows past U stay untouched
+        if flags == 3:   # two-level identity: the expert tensor is the send tensor expanded by the dedup map
+            assert torch.equal(sb[dev(want.slot_send_row).long()], eb)
+    else:
+        assert bool((sb == 0xEE).all())
+
+
+@pytest.mark.parametrize("N,k,E,D,H", [(128, 8, 256, 64, 7168), (77, 4, 16, 8, 256)])
+def test_dispatch_with_aux_plane(fusco, oracle, N, k, E, D, H):
+    rng = np.random.default_rng(H)
+    A = random_topk(rng, N, k, E)
+    q = rng.integers(0, 256, size=(N, H), dtype=np.uint8)
+    sc = rng.standard_normal((N, H // 128 if H >= 512 else 4)).astype(np.float32)
+    want = oracle.plan(A, E, D)
+    send_want, expert_want, saux_want, eaux_want = oracle.dispatch(want, q, sc)
+    L, _ = gpu_plan(fusco, A, E, D)
+    eb = torch.zeros((L.P, H), dtype=torch.uint8, device="cuda")
+    ea = torch.zeros((L.P, sc.shape[1]), dtype=torch.float32, device="cuda")
+    sb = torch.zeros((L.send_cap, H), dtype=torch.uint8, device="cuda")
+    sa = torch.zeros((L.send_cap, sc.shape[1]), dtype=torch.float32, device="cuda")
+    fusco.fusco_dispatch(L, dev(q), eb, x_aux=dev(sc), expert_aux=ea, send_buf=sb, send_aux=sa, flags=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(eb.cpu().numpy(), expert_want) and np.array_equal(ea.cpu().numpy(), eaux_want)
+    assert np.array_equal(sb[:want.U].cpu().numpy(), send_want)
+    assert np.array_equal(sa[:want.U].cpu().numpy(), saux_want)
+
+
+def _combine_case(fusco, oracle, A, E, D, y_bits_or_f32, w, out_dtype):
+    N, k = A.shape
+    L, _ = gpu_plan(fusco, A, E, D)
+    want_plan = oracle.plan(A, E, D)
+    if y_bits_or_f32.dtype == np.uint16:
+        y = bf16_dev(y_bits_or_f32)
+    else:
+        y = dev(y_bits_or_f32)
+    H = y.shape[1]
+    out = torch.full((N, H), float("nan"), dtype=out_dtype, device="cuda")
+    fusco.fusco_combine(L, y, dev(w), out)
+    torch.cuda.synchronize()
+    o32, o16 = oracle.combine_f32(y_bits_or_f32, w, want_plan.pair_slot)
+    if out_dtype == torch.float32:
+        got = out.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), o32.view(np.uint32))
+        ref = oracle.combine_f64(y_bits_or_f32, w, want_plan.pair_slot)
+        scale = oracle.combine_abs_f64(y_bits_or_f32, w, want_plan.pair_slot)
+        assert np.all(np.abs(got.astype(np.float64) - ref) <= REL_TOL * scale)
+    else:
+        assert np.array_equal(bits_host(out), o16)
+
+
+COMBINE_SHAPES = [
+    # N, k, E, D, H
+    (50, 2, 8, 4, 8), (129, 8, 64, 8, 1024), (300, 8, 256, 8, 7168), (65, 4, 16, 4, 8 * 37),
+    (40, 1, 4, 2, 512), (33, 9, 18, 6, 8 * 129), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096),
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,H", COMBINE_SHAPES)
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_combine_bf16_input_matches_oracle(fusco, oracle, N, k, E, D, H, out_dtype):
+    rng = np.random.default_rng(N * H + k)
+    A = random_topk(rng, N, k, E)
+    y = W.bf16_bits(rng.standard_normal((N * k, H)).astype(np.float32))
+    w = rng.random((N, k)).astype(np.float32)
+    w /= w.sum(1, keepdims=True)
+    _combine_case(fusco, oracle, A, E, D, y, w, out_dtype)
+
+
+@pytest.mark.parametrize("N,k,E,D,H", [(70, 8, 32, 4, 1024), (31, 3, 6, 3, 4 * 37), (16, 2, 4, 2, 4)])
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_combine_f32_input_matches_oracle(fusco, oracle, N, k, E, D, H, out_dtype):
+    rng = np.random.default_rng(N * H + k + 1)
+    A = random_topk(rng, N, k, E)
+    y = rng.standard_normal((N * k, H)).astype(np.float32)
+    w = (rng.standard_normal((N, k)) * 3).astype(np.float32)     # mixed signs: cancellation
+    _combine_case(fusco, oracle, A, E, D, y, w, out_dtype)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_dispatch_identity_combine_returns_input_exactly(fusco, k):
+    # w = 1/k is dyadic: dispatch -> identity experts -> combine reproduces x bit for bit
+    rng = np.random.default_rng(k)
+    N, E, D, H = 600, 64, 8, 2048
+    A = random_topk(rng, N, k, E)
+    xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
+    L, _ = gpu_plan(fusco, A, E, D)
+    x = bf16_dev(xb)
+    eb = torch.empty((L.P, H), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_dispatch(L, x, eb)
+    fusco.fusco_combine(L, eb, torch.full((N, k), 1.0 / k, device="cuda"), out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_host(out), xb)
+
+
+@pytest.mark.parametrize("name,n", [("tiny", 1500), ("dsv3", 700), ("qwen3", 900), ("skewed", 800)])
+def test_whole_path_on_configs_reduced(fusco, oracle, name, n):
+    """plan -> dispatch -> combine at the configurations' real row sizes, a few planner tiles."""
+    cfg = W.get_config(name).with_tokens(n)
+    A, w = W.make_routing(cfg)
+    xb = W.make_activations(cfg)
+    want = oracle.plan(A, cfg.E, cfg.D)
+    send_want, expert_want = oracle.dispatch(want, xb)
+    L, got = gpu_plan(fusco, A, cfg.E, cfg.D)
+    assert_plan_equal(got, want)
+    eb = torch.empty((L.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+    sb = torch.empty((L.send_cap, cfg.H), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_dispatch(L, bf16_dev(xb), eb, send_buf=sb, flags=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_host(eb), expert_want)
+    assert np.array_equal(bits_host(sb[:want.U]), send_want)
+    yb = W.make_expert_output(cfg)
+    for out_dtype in (torch.bfloat16, torch.float32):
+        _combine_case(fusco, oracle, A, cfg.E, cfg.D, yb, w, out_dtype)
+
+
+def test_decode_fp8_config(fusco, oracle):
+    cfg = W.get_config("decode_fp8")
+    A, w = W.make_routing(cfg)
+    q, sc = W.make_fp8_activations(cfg)
+    want = oracle.plan(A, cfg.E, cfg.D)
+    send_want, expert_want, saux_want, eaux_want = oracle.dispatch(want, q, sc)
+    L, got = gpu_plan(fusco, A, cfg.E, cfg.D)
+    assert_plan_equal(got, want)
+    eb = torch.zeros((L.P, cfg.H), dtype=torch.uint8, device="cuda")
+    ea = torch.zeros((L.P, cfg.H // 128), dtype=torch.float32, device="cuda")
+    sb = torch.zeros((L.send_cap, cfg.H), dtype=torch.uint8, device="cuda")
+    sa = torch.zeros((L.send_cap, cfg.H // 128), dtype=torch.float32, device="cuda")
+    fusco.fusco_dispatch(L, dev(q), eb, x_aux=dev(sc), expert_aux=ea, send_buf=sb, send_aux=sa, flags=3)
+    torch.cuda.synchronize()
+    assert np.array_equal(eb.cpu().numpy(), expert_want) and np.array_equal(ea.cpu().numpy(), eaux_want)
+    assert np.array_equal(sb[:want.U].cpu().numpy(), send_want) and np.array_equal(sa[:want.U].cpu().numpy(), saux_want)
+    yb = W.make_expert_output(cfg)
+    _combine_case(fusco, oracle, A, cfg.E, cfg.D, yb, w, torch.bfloat16)
+    _combine_case(fusco, oracle, A, cfg.E, cfg.D, yb, w, torch.float32)
+
+
+def test_binding_rejects_wrong_shapes(fusco):
+    L = fusco.Layout(16, 2, 4, 2)
+    x = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_dispatch(L, x, torch.zeros((31, 64), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_dispatch(L, x[:8], torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_plan(L, torch.zeros((16, 3), dtype=torch.int32, device="cuda"))
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_combine(L, torch.zeros((32, 64), dtype=torch.bfloat16, device="cuda"),
+                            torch.zeros((16, 2), device="cuda"), torch.zeros((16, 32), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(fusco.FuscoError):
+        fusco.Layout(16, 2, 4, 3)
