@@ -492,6 +492,108 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a)
     }
 }
 
+
+// ---- experimental movers (selected through environment variables while tuning) -------------
+struct XArgs {
+    DispatchArgs d;
+    const int32_t *slot_token, *exp_off, *send_src, *send_off;
+    int32_t E, D, N;
+    int32_t S;      // 64-chunk segments per row
+    int32_t WPT;    // waves per row
+    int32_t nt;     // bit 0: non-temporal loads, bit 1: non-temporal stores
+};
+
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p, bool nt) { return nt ? __builtin_nontemporal_load(p) : *p; }
+__device__ __forceinline__ void st16(u32x4 v, u32x4 *p, bool nt)
+{
+    if (nt) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// token-major, wave-centric: a wave owns UPW consecutive 64-chunk segments of one token row
+template <int UPW>
+__global__ __launch_bounds__(256) void dispatch_wave_kernel(XArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+    const int t = w / a.WPT;
+    if (t >= a.N) return;
+    const int seg0 = (w - t * a.WPT) * UPW;
+    const int C = a.d.C, Ca = a.d.Ca, Ct = C + Ca;
+    const bool ntl = a.nt & 1, nts = a.nt & 2;
+    u32x4 v[UPW];
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int c = (seg0 + i) * 64 + lane;
+        if (c < C) v[i] = ld16(a.d.x + (size_t)t * C + c, ntl);
+        else if (c < Ct) v[i] = ld16(a.d.x_aux + (size_t)t * Ca + (c - C), ntl);
+    }
+    const int32_t *slots = a.d.pair_slot + (size_t)t * a.d.k;
+    if (a.d.write_expert) {
+        for (int j = 0; j < a.d.k; ++j) {
+            const int slot = slots[j];
+            if (slot < 0) continue;
+#pragma unroll
+            for (int i = 0; i < UPW; ++i) {
+                const int c = (seg0 + i) * 64 + lane;
+                if (c < C) st16(v[i], a.d.expert_buf + (size_t)slot * C + c, nts);
+                else if (c < Ct) st16(v[i], a.d.expert_aux + (size_t)slot * Ca + (c - C), nts);
+            }
+        }
+    }
+    if (a.d.write_wire) {
+        const int32_t *rows = a.d.pair_send_row + (size_t)t * a.d.k;
+        const uint8_t *first = a.d.pair_first + (size_t)t * a.d.k;
+        for (int j = 0; j < a.d.k; ++j) {
+            if (!first[j]) continue;
+            const int row = rows[j];
+#pragma unroll
+            for (int i = 0; i < UPW; ++i) {
+                const int c = (seg0 + i) * 64 + lane;
+                if (c < C) st16(v[i], a.d.send_buf + (size_t)row * C + c, nts);
+                else if (c < Ct) st16(v[i], a.d.send_aux + (size_t)row * Ca + (c - C), nts);
+            }
+        }
+    }
+}
+
+// destination-major: a wave owns UPW consecutive segments of one destination row and pulls
+// them from the source token row; destination rows are written in address order
+template <int UPW, bool WIRE>
+__global__ __launch_bounds__(256) void dispatch_rows_kernel(XArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+    const int r = w / a.WPT;
+    const int nrows = WIRE ? a.send_off[a.D] : a.exp_off[a.E];
+    if (r >= nrows) return;
+    const int t = WIRE ? a.send_src[r] : a.slot_token[r];
+    const int seg0 = (w - r * a.WPT) * UPW;
+    const int C = a.d.C, Ca = a.d.Ca, Ct = C + Ca;
+    const bool ntl = a.nt & 1, nts = a.nt & 2;
+    u32x4 *dst = WIRE ? a.d.send_buf : a.d.expert_buf;
+    u32x4 *dst_aux = WIRE ? a.d.send_aux : a.d.expert_aux;
+    u32x4 v[UPW];
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int c = (seg0 + i) * 64 + lane;
+        if (c < C) v[i] = ld16(a.d.x + (size_t)t * C + c, ntl);
+        else if (c < Ct) v[i] = ld16(a.d.x_aux + (size_t)t * Ca + (c - C), ntl);
+    }
+#pragma unroll
+    for (int i = 0; i < UPW; ++i) {
+        const int c = (seg0 + i) * 64 + lane;
+        if (c < C) st16(v[i], dst + (size_t)r * C + c, nts);
+        else if (c < Ct) st16(v[i], dst_aux + (size_t)r * Ca + (c - C), nts);
+    }
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    return s ? atoi(s) : dflt;
+}
+
 __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -668,6 +770,43 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.write_expert = expert; a.write_wire = wire;
     const int Ct = a.C + a.Ca;
 
+    const int mode = env_int("FUSCO_DISPATCH_MODE", 0);
+    if (mode != 0) {
+        XArgs xa;
+        xa.d = a;
+        xa.slot_token = L->slot_token; xa.exp_off = L->exp_off; xa.send_src = L->send_src; xa.send_off = L->send_off;
+        xa.E = L->E; xa.D = L->D; xa.N = L->N;
+        xa.S = (Ct + 63) / 64;
+        int upw = env_int("FUSCO_UPW", 2);
+        if (upw != 1 && upw != 2 && upw != 4) upw = 2;
+        xa.WPT = (xa.S + upw - 1) / upw;
+        xa.nt = env_int("FUSCO_NT", 3);
+        hipStream_t s = (hipStream_t)stream;
+        if (mode == 1) {
+            const int64_t waves = (int64_t)L->N * xa.WPT;
+            const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+            if (upw == 1) hipLaunchKernelGGL(dispatch_wave_kernel<1>, grid, block, 0, s, xa);
+            else if (upw == 2) hipLaunchKernelGGL(dispatch_wave_kernel<2>, grid, block, 0, s, xa);
+            else hipLaunchKernelGGL(dispatch_wave_kernel<4>, grid, block, 0, s, xa);
+        } else {
+            if (expert) {
+                xa.N = L->P;
+                const int64_t waves = (int64_t)L->P * xa.WPT;
+                const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+                if (upw == 1) hipLaunchKernelGGL((dispatch_rows_kernel<1, false>), grid, block, 0, s, xa);
+                else if (upw == 2) hipLaunchKernelGGL((dispatch_rows_kernel<2, false>), grid, block, 0, s, xa);
+                else hipLaunchKernelGGL((dispatch_rows_kernel<4, false>), grid, block, 0, s, xa);
+            }
+            if (wire) {
+                const int64_t waves = (int64_t)L->send_cap * xa.WPT;
+                const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+                if (upw == 1) hipLaunchKernelGGL((dispatch_rows_kernel<1, true>), grid, block, 0, s, xa);
+                else if (upw == 2) hipLaunchKernelGGL((dispatch_rows_kernel<2, true>), grid, block, 0, s, xa);
+                else hipLaunchKernelGGL((dispatch_rows_kernel<4, true>), grid, block, 0, s, xa);
+            }
+        }
+        return launch_status();
+    }
     int cpt = Ct >= 512 ? 4 : (Ct >= 128 ? 2 : 1);
     int threads = round_up((Ct + cpt - 1) / cpt, kWave);
     if (threads > 256) threads = 256;
