@@ -83,49 +83,64 @@ __device__ __forceinline__ uint64_t same_key_lanes(int key, bool part, int nbits
     return m;
 }
 
-// True iff pair (t_local, j) is the first entry of its token whose expert lives on device d.
-__device__ __forceinline__ bool first_of_device(const int *tile_key, int row0, int j, int d, int Eloc)
+// True iff entry j of a token is the first one whose expert lives on device d.  tile_dev holds the
+// device of every pair of the tile (-1 for an invalid expert id), row0 is the token's first pair.
+__device__ __forceinline__ bool first_of_device(const int *tile_dev, int row0, int j, int d)
 {
-    for (int j2 = 0; j2 < j; ++j2) {
-        const int e2 = tile_key[row0 + j2];
-        if (e2 >= 0 && e2 / Eloc == d) return false;
-    }
+    for (int j2 = 0; j2 < j; ++j2)
+        if (tile_dev[row0 + j2] == d) return false;
     return true;
 }
 
 // Pass 1 of the multi-tile planner: per-tile counts of pairs per expert and of first
-// (token, device) appearances per device.  Counts are order-independent, so LDS atomics are safe.
+// (token, device) appearances per device.  Lanes of a wave that hold the same key are found with
+// ballots and only one of them adds their number to the LDS counter, so a popular key does not
+// serialise the wave.  Counts do not depend on the order of the additions.
 __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 {
-    __shared__ int tile_key[kTilePairs];
+    __shared__ int tile_dev[kTilePairs];
     __shared__ int hist[2 * kMaxBins + 1];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int tile = blockIdx.x;
     const int tok0 = tile * a.tpt;
     const int ntok = min(a.tpt, a.N - tok0);
     const int npairs = ntok > 0 ? ntok * a.k : 0;
     const int64_t pair0 = (int64_t)tok0 * a.k;
     const int nb = a.E + a.D;
+    const int ebits = bits_for(a.E), dbits = bits_for(a.D);
+    const uint64_t lt = ((uint64_t)1 << lane) - 1;
 
     for (int b = tid; b <= nb; b += kPlanThreads) hist[b] = 0;
-    __syncthreads();
-    for (int p = tid; p < npairs; p += kPlanThreads) {
-        const int e = a.A[pair0 + p];
+    int ekey[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = r * kPlanThreads + tid;
         int key = -1;
-        if ((unsigned)e < (unsigned)a.E) {
-            key = e;
-            atomicAdd(&hist[e], 1);
-        } else {
-            atomicAdd(&hist[nb], 1);
+        bool bad = false;
+        if (p < npairs) {
+            const int e = a.A[pair0 + p];
+            if ((unsigned)e < (unsigned)a.E) key = e;
+            else bad = true;
         }
-        tile_key[p] = key;
+        ekey[r] = key;
+        tile_dev[p] = key >= 0 ? key / a.Eloc : -1;
+        const uint64_t nbad = __builtin_amdgcn_ballot_w64(bad);
+        if (r == 0) __syncthreads();   // counters are zero from here on
+        if (nbad != 0 && lane == 0) atomicAdd(&hist[nb], __builtin_popcountll(nbad));
+        const uint64_t m = same_key_lanes(key, key >= 0, ebits);
+        if (key >= 0 && (m & lt) == 0) atomicAdd(&hist[key], __builtin_popcountll(m));
     }
     __syncthreads();
-    for (int p = tid; p < npairs; p += kPlanThreads) {
-        const int key = tile_key[p];
-        if (key < 0) continue;
-        const int tl = p / a.k, j = p - tl * a.k, d = key / a.Eloc;
-        if (first_of_device(tile_key, tl * a.k, j, d, a.Eloc)) atomicAdd(&hist[a.E + d], 1);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = r * kPlanThreads + tid;
+        int d = tile_dev[p];
+        if (d >= 0) {
+            const int tl = p / a.k, j = p - tl * a.k;
+            if (!first_of_device(tile_dev, tl * a.k, j, d)) d = -1;
+        }
+        const uint64_t m = same_key_lanes(d, d >= 0, dbits);
+        if (d >= 0 && (m & lt) == 0) atomicAdd(&hist[a.E + d], __builtin_popcountll(m));
     }
     __syncthreads();
     int32_t *out = a.tile_hist + (int64_t)tile * a.stride;
@@ -134,7 +149,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 
 // Shared LDS state of the placement kernel.
 struct PlaceLds {
-    int tile_key[kTilePairs];
+    int tile_dev[kTilePairs];
     int tile_slot[kTilePairs];
     int tile_row[kTilePairs];
     int wave_cnt[kPlanWaves][kMaxBins];
@@ -168,7 +183,9 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         const uint64_t m = same_key_lanes(key[r], part, nbits);
         const int before = part ? s.wave_cnt[wave][key[r]] : 0;
         rank[r] = before + __builtin_popcountll(m & lt);
-        __syncthreads();
+        // every lane of the wave has issued its read above before the first lane of a key group
+        // issues this write (one wave, LDS in order); the barrier orders the write before the
+        // reads of the next round
         if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = before + __builtin_popcountll(m);
         __syncthreads();
     }
@@ -181,7 +198,8 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         } else {
             const int32_t *h = a.tile_hist + hist_off + b;
             const int me = blockIdx.x;
-            for (int tl = 0; tl < a.n_tiles; ++tl) {
+#pragma unroll 16
+            for (int tl = 0; tl < a.n_tiles; ++tl) {   // independent loads, kept in flight together
                 const int v = h[(int64_t)tl * a.stride];
                 tot += v;
                 pre += tl < me ? v : 0;
@@ -245,7 +263,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 
     if (tid == 0) s.invalid = 0;
     __syncthreads();
-    int ekey[kRounds];
+    int ekey[kRounds], tl[kRounds];   // expert id and tile-local token of the thread's pairs
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
@@ -255,8 +273,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
             if ((unsigned)e < (unsigned)a.E) key = e;
             else if constexpr (SINGLE) atomicAdd(&s.invalid, 1);
         }
+        tl[r] = p / a.k;
         ekey[r] = key;
-        s.tile_key[p] = key;
+        s.tile_dev[p] = key >= 0 ? key / a.Eloc : -1;
     }
     __syncthreads();
 
@@ -271,20 +290,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
             a.pair_slot[pair0 + p] = slot[r];
             if (slot[r] >= 0) {
                 a.slot_pair[slot[r]] = (int32_t)(pair0 + p);
-                a.slot_token[slot[r]] = tok0 + p / a.k;
+                a.slot_token[slot[r]] = tok0 + tl[r];
             }
         }
     }
 
     // level 1: one send row per (token, device), taken at the device's first appearance
-    int dkey[kRounds];
+    int dkey[kRounds], jfirst[kRounds];   // jfirst: pair of the token's first entry on the same device
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
+        const int d = s.tile_dev[p];
         dkey[r] = -1;
-        if (ekey[r] >= 0) {
-            const int tl = p / a.k, j = p - tl * a.k, d = ekey[r] / a.Eloc;
-            if (first_of_device(s.tile_key, tl * a.k, j, d, a.Eloc)) dkey[r] = d;
+        jfirst[r] = p;
+        if (d >= 0) {
+            const int row0 = tl[r] * a.k;
+            for (int q = row0; q < p; ++q)
+                if (s.tile_dev[q] == d) { jfirst[r] = q; break; }
+            if (jfirst[r] == p) dkey[r] = d;
         }
     }
     int row[kRounds];
@@ -295,7 +318,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         s.tile_row[p] = row[r];
         if (p < npairs) {
             a.pair_first[pair0 + p] = row[r] >= 0 ? 1 : 0;
-            if (row[r] >= 0) a.send_src[row[r]] = tok0 + p / a.k;
+            if (row[r] >= 0) a.send_src[row[r]] = tok0 + tl[r];
         }
     }
     __syncthreads();
@@ -307,13 +330,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         if (p >= npairs) continue;
         int srow = -1;
         if (ekey[r] >= 0) {
-            const int tl = p / a.k, j = p - tl * a.k, d = ekey[r] / a.Eloc;
-            int j0 = j;
-            for (int j2 = 0; j2 < j; ++j2) {
-                const int e2 = s.tile_key[tl * a.k + j2];
-                if (e2 >= 0 && e2 / a.Eloc == d) { j0 = j2; break; }
-            }
-            srow = s.tile_row[tl * a.k + j0];
+            srow = s.tile_row[jfirst[r]];
             a.slot_send_row[s.tile_slot[p]] = srow;
         }
         a.pair_send_row[pair0 + p] = srow;
@@ -329,9 +346,27 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
-// Dispatch: one workgroup column per token; the row is held in registers between the single
-// read and the k (+ wire) writes.  Slot lookups depend only on blockIdx, so they are scalar.
+// Movers.  Both give one workgroup to one token, because HBM rewards long bursts: a row is
+// fetched or written whole by neighbouring waves of one compute unit within a short time.
+// Measured on MI355X at 14 KiB rows: scattered row reads reach the streaming read rate, scattered
+// row writes do not (about 5.2 of 6.9 TB/s), so the movers keep the scattered side of dispatch
+// as short as possible (plain cached stores, several chunks per thread in flight).
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ u32x4 load16_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// 16-byte / 8-byte stores that go to memory at system scope instead of lingering in the L2:
+// used for the token-ordered output of combine, which is never read again by this kernel.
+__device__ __forceinline__ void store16_through(u32x4 *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store8_through(u32x2 *p, u32x2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
+// Dispatch: the row is held in registers between the single read and the k (+ wire) writes.
+// Slot lookups depend only on blockIdx, so they are scalar loads.
 struct DispatchArgs {
     const u32x4 *x, *x_aux;
     u32x4 *expert_buf, *expert_aux, *send_buf, *send_aux;
@@ -352,8 +387,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int c = c0 + i * blockDim.x;
-        if (c < a.C) v[i] = __builtin_nontemporal_load(a.x + (size_t)t * a.C + c);
-        else if (c < Ct) v[i] = __builtin_nontemporal_load(a.x_aux + (size_t)t * a.Ca + (c - a.C));
+        if (c < a.C) v[i] = load16_stream(a.x + (size_t)t * a.C + c);
+        else if (c < Ct) v[i] = load16_stream(a.x_aux + (size_t)t * a.Ca + (c - a.C));
     }
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     if (a.write_expert) {
@@ -363,8 +398,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) __builtin_nontemporal_store(v[i], a.expert_buf + (size_t)slot * a.C + c);
-                else if (c < Ct) __builtin_nontemporal_store(v[i], a.expert_aux + (size_t)slot * a.Ca + (c - a.C));
+                if (c < a.C) a.expert_buf[(size_t)slot * a.C + c] = v[i];
+                else if (c < Ct) a.expert_aux[(size_t)slot * a.Ca + (c - a.C)] = v[i];
             }
         }
     }
@@ -377,18 +412,16 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) __builtin_nontemporal_store(v[i], a.send_buf + (size_t)row * a.C + c);
-                else if (c < Ct) __builtin_nontemporal_store(v[i], a.send_aux + (size_t)row * a.Ca + (c - a.C));
+                if (c < a.C) a.send_buf[(size_t)row * a.C + c] = v[i];
+                else if (c < Ct) a.send_aux[(size_t)row * a.Ca + (c - a.C)] = v[i];
             }
         }
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// Combine: one workgroup column per token; every thread owns CPT 16-byte chunks of the output
-// row, pulls the matching chunks of the token's k rows (JU rows in flight at a time) and
-// accumulates in fp32 with one fused multiply-add per term in ascending j.
-// ------------------------------------------------------------------------------------------
+// Combine: every thread owns CPT 16-byte chunks of the output row, pulls the matching chunks of
+// the token's k rows (JU rows in flight at a time) and accumulates in fp32 with one fused
+// multiply-add per term in ascending j.
 struct CombineArgs {
     const u32x4 *y;
     const float *w;
@@ -396,6 +429,7 @@ struct CombineArgs {
     const int32_t *pair_slot;
     int32_t k;
     int32_t C;   // 16-byte chunks per y row
+    int32_t st;  // tuning: 0 plain, 1 non-temporal, 2 write-through stores
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -409,8 +443,15 @@ __device__ __forceinline__ uint32_t to_bf16(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+__device__ __forceinline__ void out16(u32x4 *p, u32x4 v, int st)
+{
+    if (st == 2) store16_through(p, v);
+    else if (st == 1) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 template <bool Y_BF16, bool OUT_BF16, int CPT, int JU>
-__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a)
+__global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
 {
     constexpr int EPC = Y_BF16 ? 8 : 4;   // elements per 16-byte chunk of y
     const int t = blockIdx.x;
@@ -440,7 +481,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a)
 #pragma unroll
                     for (int i = 0; i < CPT; ++i) {
                         const int c = c0 + i * blockDim.x;
-                        if (c < a.C) v[jj][i] = __builtin_nontemporal_load(a.y + (size_t)slot * a.C + c);
+                        if (c < a.C) v[jj][i] = load16_stream(a.y + (size_t)slot * a.C + c);
                     }
                 }
             }
@@ -476,129 +517,32 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a)
             for (int q = 0; q < EPC / 2; ++q) pk[q] = to_bf16(acc[i][2 * q]) | (to_bf16(acc[i][2 * q + 1]) << 16);
             if constexpr (Y_BF16) {
                 u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
-                __builtin_nontemporal_store(o, (u32x4 *)((uint16_t *)a.out + e0));
+                out16((u32x4 *)((uint16_t *)a.out + e0), o, a.st);
             } else {
                 u32x2 o = {pk[0], pk[1]};
-                __builtin_nontemporal_store(o, (u32x2 *)((uint16_t *)a.out + e0));
+                store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
             }
         } else {
 #pragma unroll
             for (int h = 0; h < EPC / 4; ++h) {
                 u32x4 o = {__float_as_uint(acc[i][4 * h]), __float_as_uint(acc[i][4 * h + 1]),
                            __float_as_uint(acc[i][4 * h + 2]), __float_as_uint(acc[i][4 * h + 3])};
-                __builtin_nontemporal_store(o, (u32x4 *)((float *)a.out + e0) + h);
+                out16((u32x4 *)((float *)a.out + e0) + h, o, a.st);
             }
         }
     }
 }
 
-
-// ---- experimental movers (selected through environment variables while tuning) -------------
-struct XArgs {
-    DispatchArgs d;
-    const int32_t *slot_token, *exp_off, *send_src, *send_off;
-    int32_t E, D, N;
-    int32_t S;      // 64-chunk segments per row
-    int32_t WPT;    // waves per row
-    int32_t nt;     // bit 0: non-temporal loads, bit 1: non-temporal stores
-};
-
-__device__ __forceinline__ u32x4 ld16(const u32x4 *p, bool nt) { return nt ? __builtin_nontemporal_load(p) : *p; }
-__device__ __forceinline__ void st16(u32x4 v, u32x4 *p, bool nt)
+__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n)
 {
-    if (nt) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
-// token-major, wave-centric: a wave owns UPW consecutive 64-chunk segments of one token row
-template <int UPW>
-__global__ __launch_bounds__(256) void dispatch_wave_kernel(XArgs a)
-{
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
-    const int t = w / a.WPT;
-    if (t >= a.N) return;
-    const int seg0 = (w - t * a.WPT) * UPW;
-    const int C = a.d.C, Ca = a.d.Ca, Ct = C + Ca;
-    const bool ntl = a.nt & 1, nts = a.nt & 2;
-    u32x4 v[UPW];
-#pragma unroll
-    for (int i = 0; i < UPW; ++i) {
-        const int c = (seg0 + i) * 64 + lane;
-        if (c < C) v[i] = ld16(a.d.x + (size_t)t * C + c, ntl);
-        else if (c < Ct) v[i] = ld16(a.d.x_aux + (size_t)t * Ca + (c - C), ntl);
-    }
-    const int32_t *slots = a.d.pair_slot + (size_t)t * a.d.k;
-    if (a.d.write_expert) {
-        for (int j = 0; j < a.d.k; ++j) {
-            const int slot = slots[j];
-            if (slot < 0) continue;
-#pragma unroll
-            for (int i = 0; i < UPW; ++i) {
-                const int c = (seg0 + i) * 64 + lane;
-                if (c < C) st16(v[i], a.d.expert_buf + (size_t)slot * C + c, nts);
-                else if (c < Ct) st16(v[i], a.d.expert_aux + (size_t)slot * Ca + (c - C), nts);
-            }
-        }
-    }
-    if (a.d.write_wire) {
-        const int32_t *rows = a.d.pair_send_row + (size_t)t * a.d.k;
-        const uint8_t *first = a.d.pair_first + (size_t)t * a.d.k;
-        for (int j = 0; j < a.d.k; ++j) {
-            if (!first[j]) continue;
-            const int row = rows[j];
-#pragma unroll
-            for (int i = 0; i < UPW; ++i) {
-                const int c = (seg0 + i) * 64 + lane;
-                if (c < C) st16(v[i], a.d.send_buf + (size_t)row * C + c, nts);
-                else if (c < Ct) st16(v[i], a.d.send_aux + (size_t)row * Ca + (c - C), nts);
-            }
-        }
-    }
-}
-
-// destination-major: a wave owns UPW consecutive segments of one destination row and pulls
-// them from the source token row; destination rows are written in address order
-template <int UPW, bool WIRE>
-__global__ __launch_bounds__(256) void dispatch_rows_kernel(XArgs a)
-{
-    const int lane = threadIdx.x & 63;
-    const int w = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
-    const int r = w / a.WPT;
-    const int nrows = WIRE ? a.send_off[a.D] : a.exp_off[a.E];
-    if (r >= nrows) return;
-    const int t = WIRE ? a.send_src[r] : a.slot_token[r];
-    const int seg0 = (w - r * a.WPT) * UPW;
-    const int C = a.d.C, Ca = a.d.Ca, Ct = C + Ca;
-    const bool ntl = a.nt & 1, nts = a.nt & 2;
-    u32x4 *dst = WIRE ? a.d.send_buf : a.d.expert_buf;
-    u32x4 *dst_aux = WIRE ? a.d.send_aux : a.d.expert_aux;
-    u32x4 v[UPW];
-#pragma unroll
-    for (int i = 0; i < UPW; ++i) {
-        const int c = (seg0 + i) * 64 + lane;
-        if (c < C) v[i] = ld16(a.d.x + (size_t)t * C + c, ntl);
-        else if (c < Ct) v[i] = ld16(a.d.x_aux + (size_t)t * Ca + (c - C), ntl);
-    }
-#pragma unroll
-    for (int i = 0; i < UPW; ++i) {
-        const int c = (seg0 + i) * 64 + lane;
-        if (c < C) st16(v[i], dst + (size_t)r * C + c, nts);
-        else if (c < Ct) st16(v[i], dst_aux + (size_t)r * Ca + (c - C), nts);
-    }
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = load16_stream(src + i);
 }
 
 int env_int(const char *name, int dflt)
 {
     const char *s = getenv(name);
     return s ? atoi(s) : dflt;
-}
-
-__global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -614,7 +558,7 @@ bool shape_from_env(const char *name, int *threads, int *cpt)
     const long th = strtol(s, &end, 10);
     if (!end || *end != ',') return false;
     const long cp = strtol(end + 1, nullptr, 10);
-    if (th < 64 || th > 256 || th % 64 != 0) return false;
+    if (th < 64 || th > 1024 || th % 64 != 0) return false;
     if (cp != 1 && cp != 2 && cp != 4) return false;
     *threads = (int)th;
     *cpt = (int)cp;
@@ -770,47 +714,11 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.write_expert = expert; a.write_wire = wire;
     const int Ct = a.C + a.Ca;
 
-    const int mode = env_int("FUSCO_DISPATCH_MODE", 0);
-    if (mode != 0) {
-        XArgs xa;
-        xa.d = a;
-        xa.slot_token = L->slot_token; xa.exp_off = L->exp_off; xa.send_src = L->send_src; xa.send_off = L->send_off;
-        xa.E = L->E; xa.D = L->D; xa.N = L->N;
-        xa.S = (Ct + 63) / 64;
-        int upw = env_int("FUSCO_UPW", 2);
-        if (upw != 1 && upw != 2 && upw != 4) upw = 2;
-        xa.WPT = (xa.S + upw - 1) / upw;
-        xa.nt = env_int("FUSCO_NT", 3);
-        hipStream_t s = (hipStream_t)stream;
-        if (mode == 1) {
-            const int64_t waves = (int64_t)L->N * xa.WPT;
-            const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-            if (upw == 1) hipLaunchKernelGGL(dispatch_wave_kernel<1>, grid, block, 0, s, xa);
-            else if (upw == 2) hipLaunchKernelGGL(dispatch_wave_kernel<2>, grid, block, 0, s, xa);
-            else hipLaunchKernelGGL(dispatch_wave_kernel<4>, grid, block, 0, s, xa);
-        } else {
-            if (expert) {
-                xa.N = L->P;
-                const int64_t waves = (int64_t)L->P * xa.WPT;
-                const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-                if (upw == 1) hipLaunchKernelGGL((dispatch_rows_kernel<1, false>), grid, block, 0, s, xa);
-                else if (upw == 2) hipLaunchKernelGGL((dispatch_rows_kernel<2, false>), grid, block, 0, s, xa);
-                else hipLaunchKernelGGL((dispatch_rows_kernel<4, false>), grid, block, 0, s, xa);
-            }
-            if (wire) {
-                const int64_t waves = (int64_t)L->send_cap * xa.WPT;
-                const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-                if (upw == 1) hipLaunchKernelGGL((dispatch_rows_kernel<1, true>), grid, block, 0, s, xa);
-                else if (upw == 2) hipLaunchKernelGGL((dispatch_rows_kernel<2, true>), grid, block, 0, s, xa);
-                else hipLaunchKernelGGL((dispatch_rows_kernel<4, true>), grid, block, 0, s, xa);
-            }
-        }
-        return launch_status();
-    }
     int cpt = Ct >= 512 ? 4 : (Ct >= 128 ? 2 : 1);
     int threads = round_up((Ct + cpt - 1) / cpt, kWave);
     if (threads > 256) threads = 256;
     shape_from_env("FUSCO_DISPATCH_SHAPE", &threads, &cpt);
+    if (threads > 256) threads = 256;
     const int segs = (Ct + threads * cpt - 1) / (threads * cpt);
     const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
     hipStream_t s = (hipStream_t)stream;
@@ -841,9 +749,11 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
     a.pair_slot = L->pair_slot;
     a.k = L->k;
     a.C = (int32_t)(y_row / 16);
+    a.st = env_int("FUSCO_COMBINE_ST", 2);
+    // one workgroup per token whenever the row fits 1024 threads
     int cpt = 1;
     int threads = round_up(a.C, kWave);
-    if (threads > 256) threads = 256;
+    if (threads > 1024) threads = 1024;
     shape_from_env("FUSCO_COMBINE_SHAPE", &threads, &cpt);
     if (cpt > 2) cpt = 2;
     hipStream_t s = (hipStream_t)stream;
@@ -859,8 +769,8 @@ int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream)
     if (!d_dst || !d_src || bytes % 16 != 0 || !aligned16(d_dst) || !aligned16(d_src)) return FUSCO_ERR_INVALID_ARG;
     if (bytes == 0) return FUSCO_OK;
     const size_t n = bytes / 16;
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    const size_t blocks = (n + 255) / 256;
+    if (blocks > 0x7FFFFFFFu) return FUSCO_ERR_INVALID_ARG;
     hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        (u32x4 *)d_dst, (const u32x4 *)d_src, n);
     return launch_status();
