@@ -54,6 +54,7 @@ inline int num_tiles(int N, int k)
 struct PlanArgs {
     const int32_t *A;
     int32_t N, k, E, D, Eloc;
+    uint32_t k_magic, eloc_magic;   // ceil(2^20 / k), ceil(2^20 / Eloc): see div20
     int32_t tpt;      // tokens per tile
     int32_t n_tiles;
     int32_t stride;   // ints per tile in tile_hist: E expert counts, D device counts, 1 invalid count
@@ -83,13 +84,36 @@ __device__ __forceinline__ uint64_t same_key_lanes(int key, bool part, int nbits
     return m;
 }
 
-// True iff entry j of a token is the first one whose expert lives on device d.  tile_dev holds the
-// device of every pair of the tile (-1 for an invalid expert id), row0 is the token's first pair.
-__device__ __forceinline__ bool first_of_device(const int *tile_dev, int row0, int j, int d)
+// n / d for the small operands of the planner (n < 2048 with d <= 64, or n < 1024 with d <= 1024)
+// through magic = ceil(2^20 / d): the error n * (magic * d - 2^20) / (d * 2^20) stays below 1 / d.
+__device__ __forceinline__ int div20(int n, uint32_t magic) { return (int)(((uint32_t)n * magic) >> 20); }
+
+// Orders LDS traffic between the lanes of one wave (no instruction is emitted: LDS serves the
+// accesses of a wave in program order, the fences only stop the compiler from moving them).
+__device__ __forceinline__ void wave_lds_order()
 {
-    for (int j2 = 0; j2 < j; ++j2)
-        if (tile_dev[row0 + j2] == d) return false;
-    return true;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// For the pair at tile-local index p, held by lane `lane` of a round of 64 consecutive pairs:
+// the tile-local index of the first entry of the same token whose expert lives on the same device
+// d (p itself if this pair is that first appearance), or -1 if d < 0.  Must be called by all lanes.
+// `same` receives the lanes of the round with the same device.  tile_dev holds the device of every
+// pair of the tile, row0 is the token's first pair.  Entries of the token inside this round are
+// compared with ballots; only a token that straddles the round's start needs LDS reads.
+__device__ __forceinline__ int first_pair_on_device(const int *tile_dev, int p, int lane, int row0, int d, int dbits,
+                                                    uint64_t &same)
+{
+    same = same_key_lanes(d, d >= 0, dbits);
+    if (d < 0) return -1;
+    const int base = p - lane;
+    for (int q = row0; q < base; ++q)
+        if (tile_dev[q] == d) return q;
+    const int l0 = max(row0 - base, 0);
+    const uint64_t before = same & (((uint64_t)1 << lane) - 1) & ~(((uint64_t)1 << l0) - 1);
+    return before ? base + __builtin_ctzll(before) : p;
 }
 
 // Pass 1 of the multi-tile planner: per-tile counts of pairs per expert and of first
@@ -123,7 +147,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
             else bad = true;
         }
         ekey[r] = key;
-        tile_dev[p] = key >= 0 ? key / a.Eloc : -1;
+        tile_dev[p] = key >= 0 ? div20(key, a.eloc_magic) : -1;
         const uint64_t nbad = __builtin_amdgcn_ballot_w64(bad);
         if (r == 0) __syncthreads();   // counters are zero from here on
         if (nbad != 0 && lane == 0) atomicAdd(&hist[nb], __builtin_popcountll(nbad));
@@ -134,13 +158,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = r * kPlanThreads + tid;
-        int d = tile_dev[p];
-        if (d >= 0) {
-            const int tl = p / a.k, j = p - tl * a.k;
-            if (!first_of_device(tile_dev, tl * a.k, j, d)) d = -1;
-        }
-        const uint64_t m = same_key_lanes(d, d >= 0, dbits);
-        if (d >= 0 && (m & lt) == 0) atomicAdd(&hist[a.E + d], __builtin_popcountll(m));
+        const int d = tile_dev[p];
+        uint64_t same;
+        const bool first = first_pair_on_device(tile_dev, p, lane, div20(p, a.k_magic) * a.k, d, dbits, same) == p;
+        const uint64_t m = same & __builtin_amdgcn_ballot_w64(first);
+        if (first && (m & lt) == 0) atomicAdd(&hist[a.E + d], __builtin_popcountll(m));
     }
     __syncthreads();
     int32_t *out = a.tile_hist + (int64_t)tile * a.stride;
@@ -150,7 +172,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 // Shared LDS state of the placement kernel.
 struct PlaceLds {
     int tile_dev[kTilePairs];
-    int tile_slot[kTilePairs];
     int tile_row[kTilePairs];
     int wave_cnt[kPlanWaves][kMaxBins];
     int base[kMaxBins];
@@ -183,12 +204,11 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         const uint64_t m = same_key_lanes(key[r], part, nbits);
         const int before = part ? s.wave_cnt[wave][key[r]] : 0;
         rank[r] = before + __builtin_popcountll(m & lt);
-        // every lane of the wave has issued its read above before the first lane of a key group
-        // issues this write (one wave, LDS in order); the barrier orders the write before the
-        // reads of the next round
+        wave_lds_order();
         if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = before + __builtin_popcountll(m);
-        __syncthreads();
+        wave_lds_order();
     }
+    __syncthreads();
 
     // per key: total over all tiles and the part that lies in earlier tiles
     for (int b = tid; b < nb; b += kPlanThreads) {
@@ -273,9 +293,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
             if ((unsigned)e < (unsigned)a.E) key = e;
             else if constexpr (SINGLE) atomicAdd(&s.invalid, 1);
         }
-        tl[r] = p / a.k;
+        tl[r] = div20(p, a.k_magic);
         ekey[r] = key;
-        s.tile_dev[p] = key >= 0 ? key / a.Eloc : -1;
+        s.tile_dev[p] = key >= 0 ? div20(key, a.eloc_magic) : -1;
     }
     __syncthreads();
 
@@ -285,7 +305,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
-        s.tile_slot[p] = slot[r];
         if (p < npairs) {
             a.pair_slot[pair0 + p] = slot[r];
             if (slot[r] >= 0) {
@@ -296,19 +315,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
     }
 
     // level 1: one send row per (token, device), taken at the device's first appearance
-    int dkey[kRounds], jfirst[kRounds];   // jfirst: pair of the token's first entry on the same device
+    const int dbits = bits_for(a.D);
+    int dkey[kRounds], jfirst[kRounds];   // jfirst: the token's first pair on the same device
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
         const int d = s.tile_dev[p];
-        dkey[r] = -1;
-        jfirst[r] = p;
-        if (d >= 0) {
-            const int row0 = tl[r] * a.k;
-            for (int q = row0; q < p; ++q)
-                if (s.tile_dev[q] == d) { jfirst[r] = q; break; }
-            if (jfirst[r] == p) dkey[r] = d;
-        }
+        uint64_t same;
+        jfirst[r] = first_pair_on_device(s.tile_dev, p, lane, tl[r] * a.k, d, dbits, same);
+        dkey[r] = jfirst[r] == p ? d : -1;
     }
     int row[kRounds];
     rank_by_key<SINGLE>(s, a, dkey, a.D, a.E, a.send_count, a.send_off, row);
@@ -331,7 +346,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         int srow = -1;
         if (ekey[r] >= 0) {
             srow = s.tile_row[jfirst[r]];
-            a.slot_send_row[s.tile_slot[p]] = srow;
+            a.slot_send_row[slot[r]] = srow;
         }
         a.pair_send_row[pair0 + p] = srow;
     }
@@ -666,6 +681,8 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
     PlanArgs a;
     a.A = d_topk_idx;
     a.N = L->N; a.k = L->k; a.E = L->E; a.D = L->D; a.Eloc = L->E / L->D;
+    a.k_magic = ((1u << 20) + a.k - 1) / a.k;
+    a.eloc_magic = ((1u << 20) + a.Eloc - 1) / a.Eloc;
     a.tpt = tokens_per_tile(L->k);
     a.n_tiles = num_tiles(L->N, L->k);
     a.stride = L->E + L->D + 1;
