@@ -20,7 +20,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;
-constexpr int kPlanThreads = 256;                       // 4 waves per planner workgroup
+constexpr int kPlanThreads = 1024;                      // 16 waves per planner workgroup
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kTilePairs = 2048;                        // (token, expert) pairs per planner tile
 constexpr int kRounds = kTilePairs / kPlanThreads;      // 64-pair rounds per wave
@@ -103,7 +103,7 @@ __device__ __forceinline__ void wave_lds_order()
 // `same` receives the lanes of the round with the same device.  tile_dev holds the device of every
 // pair of the tile, row0 is the token's first pair.  Entries of the token inside this round are
 // compared with ballots; only a token that straddles the round's start needs LDS reads.
-__device__ __forceinline__ int first_pair_on_device(const int *tile_dev, int p, int lane, int row0, int d, int dbits,
+__device__ __forceinline__ int first_pair_on_device(const int16_t *tile_dev, int p, int lane, int row0, int d, int dbits,
                                                     uint64_t &same)
 {
     same = same_key_lanes(d, d >= 0, dbits);
@@ -122,7 +122,7 @@ __device__ __forceinline__ int first_pair_on_device(const int *tile_dev, int p, 
 // serialise the wave.  Counts do not depend on the order of the additions.
 __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 {
-    __shared__ int tile_dev[kTilePairs];
+    __shared__ int16_t tile_dev[kTilePairs];
     __shared__ int hist[2 * kMaxBins + 1];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int tile = blockIdx.x;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
             else bad = true;
         }
         ekey[r] = key;
-        tile_dev[p] = key >= 0 ? div20(key, a.eloc_magic) : -1;
+        tile_dev[p] = (int16_t)(key >= 0 ? div20(key, a.eloc_magic) : -1);
         const uint64_t nbad = __builtin_amdgcn_ballot_w64(bad);
         if (r == 0) __syncthreads();   // counters are zero from here on
         if (nbad != 0 && lane == 0) atomicAdd(&hist[nb], __builtin_popcountll(nbad));
@@ -171,10 +171,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 
 // Shared LDS state of the placement kernel.
 struct PlaceLds {
-    int tile_dev[kTilePairs];
-    int tile_row[kTilePairs];
-    int wave_cnt[kPlanWaves][kMaxBins];
-    int base[kMaxBins];
+    int16_t tile_dev[kTilePairs];              // device of every pair, -1 for an invalid expert id
+    int tile_row[kTilePairs];                  // send row of the pairs that are first appearances
+    uint16_t wave_cnt[kPlanWaves][kMaxBins];   // per wave and key: running count, then prefix over waves
+    int base[kMaxBins];                        // per key: pairs in earlier tiles, then the tile's global start
     int total[kMaxBins + 1];
     int invalid;
 };
@@ -205,7 +205,7 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         const int before = part ? s.wave_cnt[wave][key[r]] : 0;
         rank[r] = before + __builtin_popcountll(m & lt);
         wave_lds_order();
-        if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = before + __builtin_popcountll(m);
+        if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = (uint16_t)(before + __builtin_popcountll(m));
         wave_lds_order();
     }
     __syncthreads();
@@ -254,18 +254,20 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
     if (blockIdx.x == 0)
         for (int b = tid; b <= nb; b += kPlanThreads) off_out[b] = s.total[b];
 
-    // turn the per-wave counts into per-wave starting positions
+    // per key: prefix of the per-wave counts, and the global position where the tile's run starts
     for (int b = tid; b < nb; b += kPlanThreads) {
-        int run = s.total[b] + s.base[b];
+        int run = 0;
         for (int w = 0; w < kPlanWaves; ++w) {
             const int c = s.wave_cnt[w][b];
-            s.wave_cnt[w][b] = run;
+            s.wave_cnt[w][b] = (uint16_t)run;
             run += c;
         }
+        s.base[b] += s.total[b];
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) pos[r] = key[r] >= 0 ? s.wave_cnt[wave][key[r]] + rank[r] : -1;
+    for (int r = 0; r < kRounds; ++r)
+        pos[r] = key[r] >= 0 ? s.base[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
     __syncthreads();
 }
 
@@ -295,7 +297,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         }
         tl[r] = div20(p, a.k_magic);
         ekey[r] = key;
-        s.tile_dev[p] = key >= 0 ? div20(key, a.eloc_magic) : -1;
+        s.tile_dev[p] = (int16_t)(key >= 0 ? div20(key, a.eloc_magic) : -1);
     }
     __syncthreads();
 
