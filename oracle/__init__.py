@@ -39,7 +39,8 @@ def _load():
     global _lib
     if _lib is None:
         _lib = ctypes.CDLL(build())
-        for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_combine_f64",
+        for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_dispatch_rows",
+                     "fusco_oracle_combine_f64",
                      "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
@@ -120,6 +121,18 @@ def dispatch(pl: Plan, x: np.ndarray, x_aux: Optional[np.ndarray] = None):
     if x_aux is None:
         return send_buf, expert_buf
     return send_buf, expert_buf, send_aux, expert_aux
+
+
+def dispatch_rows(pl: Plan, x: np.ndarray, slots) -> np.ndarray:
+    """Rows `slots` of the expert-activation tensor, without building the whole tensor."""
+    x = np.ascontiguousarray(x)
+    slots = np.ascontiguousarray(slots, dtype=np.int32)
+    out = np.empty((len(slots), x.shape[1]), dtype=x.dtype)
+    rc = _load().fusco_oracle_dispatch_rows(_p(x), ctypes.c_int64(x.shape[1] * x.itemsize), pl.P, _p(pl.send_src),
+                                            _p(pl.slot_send_row), _p(slots), len(slots), _p(out))
+    if rc != 0:
+        raise ValueError("fusco_oracle_dispatch_rows failed with code %d" % rc)
+    return out
 
 
 def _y_args(y: np.ndarray):

@@ -197,6 +197,25 @@ int fusco_oracle_dispatch(const uint8_t *x, int64_t row_bytes,
     return ORACLE_OK;
 }
 
+/*
+ * Dispatch for a list of expert-activation rows only (for checks at sizes where the whole tensor is
+ * too large to build on the host): out row i is the payload of row slots[i], reached hop by hop as
+ * in fusco_oracle_dispatch (token of the send row that the slot's level-2 send descriptor names).
+ */
+int fusco_oracle_dispatch_rows(const uint8_t *x, int64_t row_bytes, int32_t P,
+                               const int32_t *send_src, const int32_t *slot_send_row,
+                               const int32_t *slots, int32_t n_slots, uint8_t *out)
+{
+    if (!x || !send_src || !slot_send_row || !slots || !out || row_bytes <= 0) return ORACLE_ERR_ARG;
+    for (int32_t i = 0; i < n_slots; ++i) {
+        const int32_t s = slots[i];
+        if (s < 0 || s >= P) return ORACLE_ERR_ARG;
+        const int32_t t = send_src[slot_send_row[s]];
+        memcpy(out + (int64_t)i * row_bytes, x + (int64_t)t * row_bytes, (size_t)row_bytes);
+    }
+    return ORACLE_OK;
+}
+
 static float bf16_to_float(uint16_t b)
 {
     uint32_t u = (uint32_t)b << 16;

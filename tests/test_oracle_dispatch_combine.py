@@ -31,6 +31,19 @@ def test_dispatch_is_index_select(oracle, N, k, E, D, H):
         assert np.array_equal(expert_buf[s], x[t])
 
 
+def test_dispatch_rows_equals_full_dispatch(oracle):
+    rng = np.random.default_rng(13)
+    A = random_topk(rng, 60, 4, 16)
+    x = _rand_bf16(rng, (60, 24))
+    pl = oracle.plan(A, 16, 4)
+    _, expert_buf = oracle.dispatch(pl, x)
+    slots = np.array([0, 239, 17, 17, 100], dtype=np.int32)
+    assert np.array_equal(oracle.dispatch_rows(pl, x, slots), expert_buf[slots])
+    assert np.array_equal(oracle.dispatch_rows(pl, x, slots), x[pl.slot_token[slots]])
+    with pytest.raises(ValueError):
+        oracle.dispatch_rows(pl, x, [240])
+
+
 def test_dispatch_aux_plane_follows_payload(oracle):
     rng = np.random.default_rng(11)
     A = random_topk(rng, 20, 4, 16)
