@@ -21,19 +21,31 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
+# HBM-side traffic per launch in bytes, from the rocprofv3 --pmc runs summarised in
+# profiles/bench_dsv3_hbm_traffic_pmc.txt: FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by what
+# the same counter reads for the 1 GiB plain-copy probe (1.99994 and 1.00000 KiB per count).
+MEASURED_TRAFFIC_BYTES = {
+    "dsv3": {"dispatch": 119474279 + 939524096, "combine": 941641132 + 117440512},
+}
 
-def cpu_baseline(cfg, total_tokens, A, w, xb):
-    """The CPU oracle, as it stands, on the same workload: plan + two-hop dispatch + fp64 combine."""
+
+def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=10.0, max_passes=64):
+    """The CPU oracle, as it stands, on the same workload: plan + two-hop dispatch + fp64 combine,
+    repeated until about min_seconds of CPU work have been timed."""
     import oracle
     oracle.build()
-    t0 = time.perf_counter()
-    pl = oracle.plan(A, cfg.E, cfg.D)
-    _, eb = oracle.dispatch(pl, xb)
-    oracle.combine_f64(eb, w, pl.pair_slot)
-    dt = time.perf_counter() - t0
-    return {"value": cfg.N / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of %d tokens of the %s workload, one pass (plan + dispatch + fp64 combine), %.1f s"
-                      % (cfg.N, total_tokens, cfg.name, dt),
+    passes, t0 = 0, time.perf_counter()
+    while True:
+        pl = oracle.plan(A, cfg.E, cfg.D)
+        _, eb = oracle.dispatch(pl, xb)
+        oracle.combine_f64(eb, w, pl.pair_slot)
+        passes += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or passes >= max_passes:
+            break
+    return {"value": cfg.N * passes / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of %d tokens of the %s workload, %d passes of plan + two-hop dispatch + fp64 combine "
+                      "on one host thread, %.1f s" % (cfg.N, total_tokens, cfg.name, passes, dt),
             "host_cores_available": os.cpu_count()}
 
 
@@ -45,6 +57,8 @@ def main() -> int:
     ap.add_argument("--config", default="dsv3")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (expert-parallel devices are virtual partitions of "
@@ -85,11 +99,20 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
-    # timed region: K steps, with HIP events on the launch stream around every call
+    # timed region: exactly K steps, nothing but the library's launches between the two brackets
     K = args.steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+    tokens_per_s = cfg.N * K / wall
+
+    # per-kernel durations: the same K steps again with HIP events on the launch stream around every
+    # call (an event costs about 5 us of stream time, which is why they stay out of the region above)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     for i in range(K):
         ev[i][0].record()
         fusco.fusco_plan(L, d_A)
@@ -99,12 +122,16 @@ def main() -> int:
         fusco.fusco_combine(L, d_expert, d_w, d_out)
         ev[i][3].record()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
     ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
     plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
-    ms_per_step = wall * 1e3 / K
-    tokens_per_s = cfg.N * K / wall
+
+    if args.probe_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            fusco.fusco_probe_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # sanity: the identity-expert round trip gives sum_j w_j * x[t] = x[t] up to rounding
     err = (d_out[:64].float() - d_x[:64].float()).abs().max().item()
@@ -143,7 +170,9 @@ def main() -> int:
                                "dispatch + combine (identity experts)" % (cfg.name, cfg.N, cfg.H, cfg.E, cfg.k, cfg.D),
                    "N": cfg.N, "hidden": cfg.H, "E": cfg.E, "k": cfg.k, "D": cfg.D, "seed": cfg.seed},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None},
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
+                     "timing": "mean over a second pass of the same K steps with HIP events around each call"},
         "kernels": kernels,
         "dispatch_plus_combine": {"ms": float(disp_ms + comb_ms), "tokens_per_s": cfg.N / ((disp_ms + comb_ms) * 1e-3),
                                   "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},

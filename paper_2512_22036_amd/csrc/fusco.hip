@@ -373,13 +373,16 @@ __device__ __forceinline__ u32x4 load16_stream(const u32x4 *p) { return __builti
 
 // 16-byte / 8-byte stores that go to memory at system scope instead of lingering in the L2:
 // used for the token-ordered output of combine, which is never read again by this kernel.
+// The s_nop supplies the wait states gfx9 needs between a store of more than 8 bytes and a
+// following VALU write to its data registers; the compiler adds them for its own stores but
+// cannot see into this statement.
 __device__ __forceinline__ void store16_through(u32x4 *p, u32x4 v)
 {
-    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void store8_through(u32x2 *p, u32x2 v)
 {
-    asm volatile("global_store_dwordx2 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
 // Dispatch: the row is held in registers between the single read and the k (+ wire) writes.
@@ -446,7 +449,6 @@ struct CombineArgs {
     const int32_t *pair_slot;
     int32_t k;
     int32_t C;   // 16-byte chunks per y row
-    int32_t st;  // tuning: 0 plain, 1 non-temporal, 2 write-through stores
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -460,18 +462,13 @@ __device__ __forceinline__ uint32_t to_bf16(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-__device__ __forceinline__ void out16(u32x4 *p, u32x4 v, int st)
-{
-    if (st == 2) store16_through(p, v);
-    else if (st == 1) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 template <bool Y_BF16, bool OUT_BF16, int CPT, int JU>
 __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
 {
     constexpr int EPC = Y_BF16 ? 8 : 4;   // elements per 16-byte chunk of y
-    const int t = blockIdx.x;
+    // last token first: when combine follows dispatch, the rows written last are the ones still in
+    // the memory-side cache
+    const int t = gridDim.x - 1 - blockIdx.x;
     const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     const float *wt = a.w + (size_t)t * a.k;
@@ -534,7 +531,7 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
             for (int q = 0; q < EPC / 2; ++q) pk[q] = to_bf16(acc[i][2 * q]) | (to_bf16(acc[i][2 * q + 1]) << 16);
             if constexpr (Y_BF16) {
                 u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
-                out16((u32x4 *)((uint16_t *)a.out + e0), o, a.st);
+                store16_through((u32x4 *)((uint16_t *)a.out + e0), o);
             } else {
                 u32x2 o = {pk[0], pk[1]};
                 store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
@@ -544,7 +541,7 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
             for (int h = 0; h < EPC / 4; ++h) {
                 u32x4 o = {__float_as_uint(acc[i][4 * h]), __float_as_uint(acc[i][4 * h + 1]),
                            __float_as_uint(acc[i][4 * h + 2]), __float_as_uint(acc[i][4 * h + 3])};
-                out16((u32x4 *)((float *)a.out + e0) + h, o, a.st);
+                store16_through((u32x4 *)((float *)a.out + e0) + h, o);
             }
         }
     }
@@ -554,12 +551,6 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = load16_stream(src + i);
-}
-
-int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    return s ? atoi(s) : dflt;
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
@@ -768,7 +759,6 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
     a.pair_slot = L->pair_slot;
     a.k = L->k;
     a.C = (int32_t)(y_row / 16);
-    a.st = env_int("FUSCO_COMBINE_ST", 2);
     // one workgroup per token whenever the row fits 1024 threads
     int cpt = 1;
     int threads = round_up(a.C, kWave);
