@@ -49,6 +49,37 @@ def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=10.0, max_passes=64):
             "host_cores_available": os.cpu_count()}
 
 
+def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
+    """Event-timed means of the paths that are not the headline: the two-hop dispatch (level 1 then level 2
+    as separate passes) and the disaggregated baseline (pack by device, exchange copy, re-pack by expert, and
+    the mirror for combine).  Same inputs, same outputs as the fused step."""
+    def mean_ms(fn):
+        for _ in range(3):
+            fn()
+        e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in e:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in e) / reps
+
+    d_send = torch.empty((L.send_cap, cfg.H), dtype=torch.bfloat16, device="cuda")
+    two_hop = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=fusco.DISPATCH_TWO_HOP))
+    wire = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=3))
+    del d_send
+    Lr = fusco.Layout(cfg.N, cfg.k, cfg.D, cfg.D)
+    d_dev = torch.empty_like(d_A)
+    rank_plan = mean_ms(lambda: fusco.fusco_disaggregated_plan(Lr, L, d_A, d_dev))
+    st_a = torch.empty_like(d_expert)
+    st_b = torch.empty_like(d_expert)
+    dis_d = mean_ms(lambda: fusco.fusco_disaggregated_dispatch(L, Lr, d_x, st_a, st_b, d_expert))
+    dis_c = mean_ms(lambda: fusco.fusco_disaggregated_combine(L, Lr, d_expert, d_w, st_a, st_b, d_out))
+    return {"two_hop_dispatch_ms": two_hop, "fused_dispatch_with_wire_tensor_ms": wire,
+            "disaggregated_plan_extra_ms": rank_plan, "disaggregated_dispatch_ms": dis_d,
+            "disaggregated_combine_ms": dis_c, "reps": reps}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +88,8 @@ def main() -> int:
     ap.add_argument("--config", default="dsv3")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip timing the two-hop dispatch and the disaggregated multi-stage baseline")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -125,6 +158,10 @@ def main() -> int:
     ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
     plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
 
+    variants = None
+    if not args.no_variants:
+        variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
+
     if args.probe_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -178,6 +215,12 @@ def main() -> int:
                                   "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},
         "invalid_ids": status,
     }
+    if variants is not None:
+        fused = float(disp_ms + comb_ms)
+        variants["fused_dispatch_plus_combine_ms"] = fused
+        variants["fused_speedup_over_disaggregated"] = (variants["disaggregated_dispatch_ms"]
+                                                        + variants["disaggregated_combine_ms"]) / fused
+        result["variants"] = variants
     if not args.no_cpu_baseline:
         n = args.cpu_sample_tokens or cfg.N
         sub = cfg.with_tokens(min(n, cfg.N))

@@ -47,6 +47,7 @@ extern "C" {
 /* flags of fusco_dispatch (0 means FUSCO_DISPATCH_EXPERT) */
 #define FUSCO_DISPATCH_EXPERT 1u /* write the expert-activation tensor (level 2 result)       */
 #define FUSCO_DISPATCH_WIRE 2u   /* write the deduplicated per-device receive tensors (level 1) */
+#define FUSCO_DISPATCH_TWO_HOP 4u /* hop by hop: x -> receive tensors -> expert tensor (implies both) */
 
 /*
  * Layout descriptor: the two-level descriptor lists of the paper's Communication Planner
@@ -122,6 +123,11 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
  * d_expert_aux: [P, aux_row_bytes]; d_send_buf: [send_cap, row_bytes], d_send_aux likewise; rows
  * >= U of the send buffers are not written.  Buffers of a plane that is not requested by `flags`
  * may be NULL.
+ * FUSCO_DISPATCH_TWO_HOP executes the two descriptor levels one after the other, as the planner
+ * describes them (section 3.3): first one row per (token, device) into the receive tensors, then
+ *     expert_buf[s] = send_buf[slot_send_row[s]]
+ * for every assigned slot.  Both tensors are written and hold the same bytes as in the fused mode;
+ * the extra pass costs U + P more row reads.
  */
 int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
@@ -137,6 +143,33 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
  */
 int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, void *d_out,
                   int out_dtype, int32_t H, uint32_t flags, void *stream);
+
+/*
+ * Disaggregated baseline: the multi-stage shuffle the paper starts from (section 1: rearrange by
+ * destination rank, all-to-all, rearrange by expert, and the symmetric reverse; section 5.4, the
+ * "dComm-off" ablation, performs the rearrangements explicitly around the transfer).  Each stage is
+ * a separate pass over the whole buffer; no deduplication (one row per (token, expert) pair).  It
+ * exists to measure what fusing buys on this GPU and produces the same expert tensor / output.
+ *
+ * fusco_disaggregated_plan fills Lr, a second layout bound by the caller with
+ * fusco_layout_bind(Lr, N, k, D, D, ...): the stable order of the pairs by destination device
+ * ("rank-major": Lr->pair_slot is the pair's row, Lr->slot_token its token).  d_topk_dev: [N, k]
+ * int32 scratch that receives the device of every pair.  d_scratch as for fusco_plan with (N,k,D,D).
+ * L must already hold the plan of the same d_topk_idx.
+ *
+ * fusco_disaggregated_dispatch: stage_a[r] = x[token of rank row r]; stage_b = stage_a (the
+ * exchange between virtual devices, a contiguous copy); expert_buf[s] = stage_b[rank row of slot s].
+ * fusco_disaggregated_combine: stage_b[r] = y[slot of rank row r]; stage_a = stage_b;
+ * out[t] = sum_j w[t,j] * stage_a[rank row of (t,j)] (same arithmetic as fusco_combine).
+ * d_stage_a, d_stage_b: [P, row] scratch tensors, overwritten.
+ */
+int fusco_disaggregated_plan(fusco_layout *Lr, const fusco_layout *L, const int32_t *d_topk_idx, int32_t *d_topk_dev,
+                             void *d_scratch, size_t scratch_bytes, void *stream);
+int fusco_disaggregated_dispatch(const fusco_layout *L, const fusco_layout *Lr, const void *d_x, size_t row_bytes,
+                                 void *d_stage_a, void *d_stage_b, void *d_expert_buf, void *stream);
+int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, const void *d_y, int y_dtype,
+                                const float *d_w, void *d_stage_a, void *d_stage_b, void *d_out, int out_dtype,
+                                int32_t H, void *stream);
 
 /*
  * Measurement aid: plain device copy of `bytes` bytes (multiple of 16) with the same 16-byte

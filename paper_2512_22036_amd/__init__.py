@@ -5,10 +5,12 @@ include/fusco.h; this package is a thin ctypes binding with the same names.  PyT
 device memory and streams only.  There is no CPU or PyTorch fallback: without the built library
 every call raises.
 """
-from .binding import (BF16, F32, DISPATCH_EXPERT, DISPATCH_WIRE, FuscoError, Layout, library_path,
+from .binding import (BF16, F32, DISPATCH_EXPERT, DISPATCH_WIRE, DISPATCH_TWO_HOP, FuscoError, Layout, library_path,
                       load_library, fusco_version, fusco_plan, fusco_dispatch, fusco_combine,
-                      fusco_probe_copy)
+                      fusco_probe_copy, fusco_disaggregated_plan, fusco_disaggregated_dispatch,
+                      fusco_disaggregated_combine)
 
-__all__ = ["BF16", "F32", "DISPATCH_EXPERT", "DISPATCH_WIRE", "FuscoError", "Layout", "library_path",
-           "load_library", "fusco_version", "fusco_plan", "fusco_dispatch", "fusco_combine",
-           "fusco_probe_copy"]
+__all__ = ["BF16", "F32", "DISPATCH_EXPERT", "DISPATCH_WIRE", "DISPATCH_TWO_HOP", "FuscoError", "Layout",
+           "library_path", "load_library", "fusco_version", "fusco_plan", "fusco_dispatch", "fusco_combine",
+           "fusco_probe_copy", "fusco_disaggregated_plan", "fusco_disaggregated_dispatch",
+           "fusco_disaggregated_combine"]

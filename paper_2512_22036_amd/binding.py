@@ -15,13 +15,14 @@ from typing import Optional
 import torch
 
 BF16, F32 = 0, 1
-DISPATCH_EXPERT, DISPATCH_WIRE = 1, 2
+DISPATCH_EXPERT, DISPATCH_WIRE, DISPATCH_TWO_HOP = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy")
+           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy",
+           "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
 
 class FuscoError(RuntimeError):
@@ -75,6 +76,13 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
+    lp = ctypes.POINTER(_CLayout)
+    lib.fusco_disaggregated_plan.restype = ctypes.c_int
+    lib.fusco_disaggregated_plan.argtypes = [lp, lp, vp, vp, vp, sz, vp]
+    lib.fusco_disaggregated_dispatch.restype = ctypes.c_int
+    lib.fusco_disaggregated_dispatch.argtypes = [lp, lp, vp, sz, vp, vp, vp, vp]
+    lib.fusco_disaggregated_combine.restype = ctypes.c_int
+    lib.fusco_disaggregated_combine.argtypes = [lp, lp, vp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int, i32, vp]
     _lib = lib
     return lib
 
@@ -164,6 +172,8 @@ def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.T
     rb = _rows(x, "x", layout.N)
     ab = _rows(x_aux, "x_aux", layout.N) if x_aux is not None else 0
     eff = flags or DISPATCH_EXPERT
+    if eff & DISPATCH_TWO_HOP:
+        eff |= DISPATCH_EXPERT | DISPATCH_WIRE
     if eff & DISPATCH_EXPERT:
         if expert_buf is None:
             raise FuscoError("expert_buf is required")
@@ -215,3 +225,46 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise FuscoError("dst is smaller than src")
     _check(load_library().fusco_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
            "fusco_probe_copy")
+
+
+def fusco_disaggregated_plan(rank_layout: Layout, layout: Layout, topk_idx: torch.Tensor, topk_dev: torch.Tensor,
+                             stream=None) -> None:
+    """rank_layout must be Layout(N, k, D, D); topk_dev is an int32 [N, k] scratch tensor."""
+    for t, name in ((topk_idx, "topk_idx"), (topk_dev, "topk_dev")):
+        if (not t.is_cuda or t.dtype != torch.int32 or not t.is_contiguous()
+                or tuple(t.shape) != (layout.N, layout.k)):
+            raise FuscoError("%s must be a contiguous int32 device tensor of shape [N, k]" % name)
+    _check(load_library().fusco_disaggregated_plan(ctypes.byref(rank_layout.c), ctypes.byref(layout.c),
+                                                   topk_idx.data_ptr(), topk_dev.data_ptr(),
+                                                   rank_layout.scratch.data_ptr(), rank_layout.scratch.numel(),
+                                                   _stream(stream)), "fusco_disaggregated_plan")
+
+
+def fusco_disaggregated_dispatch(layout: Layout, rank_layout: Layout, x: torch.Tensor, stage_a: torch.Tensor,
+                                 stage_b: torch.Tensor, expert_buf: torch.Tensor, stream=None) -> None:
+    rb = _rows(x, "x", layout.N)
+    for t, name in ((stage_a, "stage_a"), (stage_b, "stage_b"), (expert_buf, "expert_buf")):
+        _rows(t, name, layout.P, rb)
+    _check(load_library().fusco_disaggregated_dispatch(ctypes.byref(layout.c), ctypes.byref(rank_layout.c),
+                                                       x.data_ptr(), rb, stage_a.data_ptr(), stage_b.data_ptr(),
+                                                       expert_buf.data_ptr(), _stream(stream)),
+           "fusco_disaggregated_dispatch")
+
+
+def fusco_disaggregated_combine(layout: Layout, rank_layout: Layout, y: torch.Tensor, w: torch.Tensor,
+                                stage_a: torch.Tensor, stage_b: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    rb = _rows(y, "y", layout.P)
+    H = y.shape[1]
+    for t, name in ((stage_a, "stage_a"), (stage_b, "stage_b")):
+        _rows(t, name, layout.P, rb)
+    _rows(out, "out", layout.N)
+    if out.shape[1] != H:
+        raise FuscoError("out must have %d columns" % H)
+    if (not w.is_cuda or w.dtype != torch.float32 or not w.is_contiguous()
+            or tuple(w.shape) != (layout.N, layout.k)):
+        raise FuscoError("w must be a contiguous float32 device tensor of shape [N, k]")
+    _check(load_library().fusco_disaggregated_combine(ctypes.byref(layout.c), ctypes.byref(rank_layout.c),
+                                                      y.data_ptr(), _dtype_code(y, "y"), w.data_ptr(),
+                                                      stage_a.data_ptr(), stage_b.data_ptr(), out.data_ptr(),
+                                                      _dtype_code(out, "out"), H, _stream(stream)),
+           "fusco_disaggregated_combine")

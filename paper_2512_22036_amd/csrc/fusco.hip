@@ -547,6 +547,49 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
     }
 }
 
+// Row gather in destination order: dst[r] = src[idx2 ? idx2[idx1[r]] : idx1[r]] for r < n_rows, one
+// workgroup column per destination row.  n_rows_dev, when set, is a device-resident row count that
+// caps n_rows (data-dependent lengths such as U).  Used by the two-hop dispatch (second hop) and by
+// the disaggregated baseline, whose every stage is such a pass over the whole buffer.
+struct GatherArgs {
+    const u32x4 *src;
+    u32x4 *dst;
+    const int32_t *idx1, *idx2;
+    const int32_t *n_rows_dev;
+    int32_t C;   // 16-byte chunks per row
+};
+
+template <int CPT, bool STREAM_LOAD>
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a)
+{
+    const int r = blockIdx.x;
+    if (a.n_rows_dev && r >= *a.n_rows_dev) return;
+    int q = a.idx1[r];
+    if (q >= 0 && a.idx2) q = a.idx2[q];
+    if (q < 0) return;
+    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    u32x4 v[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c < a.C) v[i] = STREAM_LOAD ? load16_stream(a.src + (size_t)q * a.C + c) : a.src[(size_t)q * a.C + c];
+    }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c < a.C) a.dst[(size_t)r * a.C + c] = v[i];
+    }
+}
+
+// dev[p] = device of expert A[p] (or -1 for an id outside [0, E)): the key of the rank-major order
+__global__ __launch_bounds__(256) void expert_to_device_kernel(int32_t *dev, const int32_t *A, int64_t n, int E, int Eloc)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const int e = A[p];
+    dev[p] = (unsigned)e < (unsigned)E ? e / Eloc : -1;
+}
+
 __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -585,6 +628,69 @@ void launch_combine(const CombineArgs &a, int N, int threads, int cpt, hipStream
     const dim3 grid((unsigned)N, (unsigned)segs), block((unsigned)threads);
     if (cpt == 1) hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 1, 8>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 2, 8>), grid, block, 0, s, a);
+}
+
+// dst[r] = src[index(r)] for n_rows destination rows of C chunks (see gather_rows_kernel)
+template <bool STREAM_LOAD>
+void launch_gather(const void *src, void *dst, const int32_t *idx1, const int32_t *idx2, const int32_t *n_rows_dev,
+                   int n_rows, int C, hipStream_t s)
+{
+    if (n_rows <= 0 || C <= 0) return;
+    GatherArgs a;
+    a.src = (const u32x4 *)src; a.dst = (u32x4 *)dst;
+    a.idx1 = idx1; a.idx2 = idx2; a.n_rows_dev = n_rows_dev; a.C = C;
+    const int cpt = C >= 512 ? 4 : (C >= 128 ? 2 : 1);
+    int threads = round_up((C + cpt - 1) / cpt, kWave);
+    if (threads > 256) threads = 256;
+    const int segs = (C + threads * cpt - 1) / (threads * cpt);
+    const dim3 grid((unsigned)n_rows, (unsigned)segs), block((unsigned)threads);
+    switch (cpt) {
+    case 1: hipLaunchKernelGGL((gather_rows_kernel<1, STREAM_LOAD>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((gather_rows_kernel<2, STREAM_LOAD>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gather_rows_kernel<4, STREAM_LOAD>), grid, block, 0, s, a); break;
+    }
+}
+
+void launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    const size_t n = bytes / 16;
+    if (n == 0) return;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (u32x4 *)dst,
+                       (const u32x4 *)src, n);
+}
+
+int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_out, int out_dtype, int32_t H)
+{
+    if (!d_y || !d_w || !d_out || H <= 0) return FUSCO_ERR_INVALID_ARG;
+    if ((y_dtype != FUSCO_BF16 && y_dtype != FUSCO_F32) || (out_dtype != FUSCO_BF16 && out_dtype != FUSCO_F32))
+        return FUSCO_ERR_UNSUPPORTED;
+    const size_t y_row = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
+    if (y_row % 16 != 0 || y_row / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
+    if (!aligned16(d_y) || !aligned16(d_out) || ((uintptr_t)d_w & 3u)) return FUSCO_ERR_INVALID_ARG;
+    return FUSCO_OK;
+}
+
+// out[t] = sum_j w[t, j] * y[pair_slot[t * k + j]] for N tokens; arguments already checked
+void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int y_dtype, const float *d_w,
+                    void *d_out, int out_dtype, int32_t H, hipStream_t s)
+{
+    CombineArgs a;
+    a.y = (const u32x4 *)d_y;
+    a.w = d_w;
+    a.out = d_out;
+    a.pair_slot = pair_slot;
+    a.k = k;
+    a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
+    // one workgroup per token whenever the row fits 1024 threads
+    int cpt = 1;
+    int threads = round_up(a.C, kWave);
+    if (threads > 1024) threads = 1024;
+    shape_from_env("FUSCO_COMBINE_SHAPE", &threads, &cpt);
+    if (cpt > 2) cpt = 2;
+    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, cpt, s);
+    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, cpt, s);
+    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, cpt, s);
+    else launch_combine<false, false>(a, N, threads, cpt, s);
 }
 
 }   // namespace
@@ -700,7 +806,9 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
 {
     if (!layout_ok(L) || !d_x) return FUSCO_ERR_INVALID_ARG;
     if (flags == 0) flags = FUSCO_DISPATCH_EXPERT;
-    if (flags & ~(FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE)) return FUSCO_ERR_UNSUPPORTED;
+    if (flags & ~(FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE | FUSCO_DISPATCH_TWO_HOP)) return FUSCO_ERR_UNSUPPORTED;
+    const bool two_hop = flags & FUSCO_DISPATCH_TWO_HOP;
+    if (two_hop) flags |= FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE;   // both tensors are produced
     const bool expert = flags & FUSCO_DISPATCH_EXPERT, wire = flags & FUSCO_DISPATCH_WIRE;
     if (row_bytes == 0 || row_bytes % 16 != 0 || aux_row_bytes % 16 != 0) return FUSCO_ERR_INVALID_ARG;
     if ((row_bytes + aux_row_bytes) / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
@@ -721,7 +829,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.k = L->k;
     a.C = (int32_t)(row_bytes / 16);
     a.Ca = (int32_t)(aux_row_bytes / 16);
-    a.write_expert = expert; a.write_wire = wire;
+    a.write_expert = expert && !two_hop; a.write_wire = wire;
     const int Ct = a.C + a.Ca;
 
     int cpt = Ct >= 512 ? 4 : (Ct >= 128 ? 2 : 1);
@@ -737,39 +845,79 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     case 2: hipLaunchKernelGGL(dispatch_kernel<2>, grid, block, 0, s, a); break;
     default: hipLaunchKernelGGL(dispatch_kernel<4>, grid, block, 0, s, a); break;
     }
+    if (two_hop) {
+        // second hop: every row of the expert tensor is pulled from its token's row in the receive
+        // tensor of the expert's device (level-2 send descriptor), over the exp_off[E] assigned rows
+        launch_gather<false>(d_send_buf, d_expert_buf, L->slot_send_row, nullptr, L->exp_off + L->E, L->P, a.C, s);
+        if (a.Ca)
+            launch_gather<false>(d_send_aux, d_expert_aux, L->slot_send_row, nullptr, L->exp_off + L->E, L->P, a.Ca, s);
+    }
     return launch_status();
 }
 
 int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, void *d_out,
                   int out_dtype, int32_t H, uint32_t flags, void *stream)
 {
-    if (!layout_ok(L) || !d_y || !d_w || !d_out || H <= 0) return FUSCO_ERR_INVALID_ARG;
+    if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
     if (flags != 0) return FUSCO_ERR_UNSUPPORTED;
-    if ((y_dtype != FUSCO_BF16 && y_dtype != FUSCO_F32) || (out_dtype != FUSCO_BF16 && out_dtype != FUSCO_F32))
-        return FUSCO_ERR_UNSUPPORTED;
-    const size_t y_row = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
-    if (y_row % 16 != 0 || y_row / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
-    if (!aligned16(d_y) || !aligned16(d_out) || ((uintptr_t)d_w & 3u)) return FUSCO_ERR_INVALID_ARG;
-    if (L->N == 0) return FUSCO_OK;
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
+    if (rc != FUSCO_OK || L->N == 0) return rc;
+    combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream);
+    return launch_status();
+}
 
-    CombineArgs a;
-    a.y = (const u32x4 *)d_y;
-    a.w = d_w;
-    a.out = d_out;
-    a.pair_slot = L->pair_slot;
-    a.k = L->k;
-    a.C = (int32_t)(y_row / 16);
-    // one workgroup per token whenever the row fits 1024 threads
-    int cpt = 1;
-    int threads = round_up(a.C, kWave);
-    if (threads > 1024) threads = 1024;
-    shape_from_env("FUSCO_COMBINE_SHAPE", &threads, &cpt);
-    if (cpt > 2) cpt = 2;
+int fusco_disaggregated_plan(fusco_layout *Lr, const fusco_layout *L, const int32_t *d_topk_idx, int32_t *d_topk_dev,
+                             void *d_scratch, size_t scratch_bytes, void *stream)
+{
+    if (!layout_ok(L) || !layout_ok(Lr) || (!d_topk_idx && L->N > 0) || (!d_topk_dev && L->N > 0))
+        return FUSCO_ERR_INVALID_ARG;
+    if (Lr->N != L->N || Lr->k != L->k || Lr->E != L->D || Lr->D != L->D) return FUSCO_ERR_INVALID_ARG;
+    if (scratch_bytes < fusco_scratch_bytes(Lr->N, Lr->k, Lr->E, Lr->D)) return FUSCO_ERR_WORKSPACE;
+    if (L->P > 0)
+        hipLaunchKernelGGL(expert_to_device_kernel, dim3((unsigned)((L->P + 255) / 256)), dim3(256), 0,
+                           (hipStream_t)stream, d_topk_dev, d_topk_idx, (int64_t)L->P, L->E, L->E / L->D);
+    return fusco_plan(Lr, d_topk_dev, d_scratch, scratch_bytes, stream);
+}
+
+static bool rank_layout_matches(const fusco_layout *L, const fusco_layout *Lr)
+{
+    return layout_ok(L) && layout_ok(Lr) && Lr->N == L->N && Lr->k == L->k && Lr->E == L->D && Lr->D == L->D;
+}
+
+int fusco_disaggregated_dispatch(const fusco_layout *L, const fusco_layout *Lr, const void *d_x, size_t row_bytes,
+                                 void *d_stage_a, void *d_stage_b, void *d_expert_buf, void *stream)
+{
+    if (!rank_layout_matches(L, Lr) || !d_x || !d_stage_a || !d_stage_b || !d_expert_buf) return FUSCO_ERR_INVALID_ARG;
+    if (row_bytes == 0 || row_bytes % 16 != 0 || row_bytes / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
+    if (!aligned16(d_x) || !aligned16(d_stage_a) || !aligned16(d_stage_b) || !aligned16(d_expert_buf))
+        return FUSCO_ERR_INVALID_ARG;
+    if (L->N == 0) return FUSCO_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, L->N, threads, cpt, s);
-    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, L->N, threads, cpt, s);
-    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, L->N, threads, cpt, s);
-    else launch_combine<false, false>(a, L->N, threads, cpt, s);
+    const int C = (int)(row_bytes / 16);
+    // 1) rearrange by destination device: one row per (token, expert) pair, device-major, token order
+    launch_gather<false>(d_x, d_stage_a, Lr->slot_token, nullptr, Lr->exp_off + Lr->E, L->P, C, s);
+    // 2) the exchange between the virtual devices: a contiguous copy of the packed buffer
+    launch_copy(d_stage_b, d_stage_a, (size_t)L->P * row_bytes, s);
+    // 3) rearrange the received rows by expert
+    launch_gather<true>(d_stage_b, d_expert_buf, L->slot_pair, Lr->pair_slot, L->exp_off + L->E, L->P, C, s);
+    return launch_status();
+}
+
+int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, const void *d_y, int y_dtype,
+                                const float *d_w, void *d_stage_a, void *d_stage_b, void *d_out, int out_dtype,
+                                int32_t H, void *stream)
+{
+    if (!rank_layout_matches(L, Lr) || !d_stage_a || !d_stage_b) return FUSCO_ERR_INVALID_ARG;
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
+    if (rc != FUSCO_OK) return rc;
+    if (!aligned16(d_stage_a) || !aligned16(d_stage_b)) return FUSCO_ERR_INVALID_ARG;
+    if (L->N == 0) return FUSCO_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const size_t row_bytes = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
+    // 3') expert order -> rank order, 2') exchange copy, 1') un-permute with the weighted sum
+    launch_gather<true>(d_y, d_stage_b, Lr->slot_pair, L->pair_slot, Lr->exp_off + Lr->E, L->P, (int)(row_bytes / 16), s);
+    launch_copy(d_stage_a, d_stage_b, (size_t)L->P * row_bytes, s);
+    combine_launch(Lr->pair_slot, L->N, L->k, d_stage_a, y_dtype, d_w, d_out, out_dtype, H, s);
     return launch_status();
 }
 

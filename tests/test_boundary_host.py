@@ -101,6 +101,7 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert d(buf, 64, None, 0, buf, None, None, None, 2, None) == -1             # wire without send buffer
     assert d(buf + 4, 64, None, 0, buf, None, None, None, 0, None) == -1         # misaligned
     assert d(buf, 64, None, 0, buf, None, None, None, 8, None) == -3             # unknown flag
+    assert d(buf, 64, None, 0, buf, None, None, None, 4, None) == -1             # two-hop needs the send buffer
     assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
     # combine
     c = lambda *a: lib.fusco_combine(ctypes.byref(L), *a)
@@ -114,6 +115,25 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert c(buf, 0, buf, buf, 7, 64, 0, None) == -3
     assert c(buf, 0, buf, buf, 0, 64, 1, None) == -3          # flags must be 0
     assert c(buf + 8, 0, buf, buf, 0, 64, 0, None) == -1
+    # disaggregated baseline
+    Lr = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(Lr), N, k, D, D, base + (1 << 24), lib.fusco_layout_bytes(N, k, D, D)) == 0
+    rscratch = lib.fusco_scratch_bytes(N, k, D, D)
+    assert lib.fusco_disaggregated_plan(ctypes.byref(Lr), ctypes.byref(L), None, buf, buf, rscratch, None) == -1
+    assert lib.fusco_disaggregated_plan(ctypes.byref(Lr), ctypes.byref(L), buf, None, buf, rscratch, None) == -1
+    assert lib.fusco_disaggregated_plan(ctypes.byref(L), ctypes.byref(L), buf, buf, buf, rscratch, None) == -1   # not (N,k,D,D)
+    assert lib.fusco_disaggregated_plan(ctypes.byref(Lr), ctypes.byref(L), buf, buf, buf, rscratch - 1, None) == -2
+    dd = lambda *a: lib.fusco_disaggregated_dispatch(ctypes.byref(L), ctypes.byref(Lr), *a)
+    assert dd(None, 64, buf, buf, buf, None) == -1
+    assert dd(buf, 40, buf, buf, buf, None) == -1
+    assert dd(buf, 64, None, buf, buf, None) == -1
+    assert dd(buf, 64, buf, buf + 8, buf, None) == -1
+    assert lib.fusco_disaggregated_dispatch(ctypes.byref(L), ctypes.byref(L), buf, 64, buf, buf, buf, None) == -1
+    dc = lambda *a: lib.fusco_disaggregated_combine(ctypes.byref(L), ctypes.byref(Lr), *a)
+    assert dc(buf, 0, buf, None, buf, buf, 0, 64, None) == -1
+    assert dc(buf, 0, buf, buf, buf, None, 0, 64, None) == -1
+    assert dc(buf, 3, buf, buf, buf, buf, 0, 64, None) == -3
+    assert dc(buf, 0, buf, buf, buf, buf, 0, 12, None) == -1
     # probe copy
     assert lib.fusco_probe_copy(None, buf, 64, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4, 64, None) == -1

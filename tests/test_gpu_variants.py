@@ -1,0 +1,138 @@
+"""Two-hop dispatch (the two descriptor levels executed one after the other) and the disaggregated
+multi-stage baseline must produce the same bytes as the oracle and as the fused path."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from definitions import random_topk
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fusco():
+    import paper_2512_22036_amd as f
+    f.load_library()
+    assert torch.cuda.is_available()
+    return f
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bf16_dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def bits_host(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+SHAPES = [(33, 2, 8, 4, 16), (257, 8, 64, 8, 2048), (300, 8, 256, 8, 14336), (513, 2, 16, 4, 16 * 37),
+          (64, 3, 6, 3, 16 * 129), (40, 8, 32, 32, 16 * 1025), (1, 1, 1, 1, 4096), (700, 4, 16, 1, 256)]
+
+
+@pytest.mark.parametrize("N,k,E,D,row_bytes", SHAPES)
+def test_two_hop_dispatch_matches_oracle(fusco, oracle, N, k, E, D, row_bytes):
+    rng = np.random.default_rng(N + row_bytes + 1)
+    A = random_topk(rng, N, k, E)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    want = oracle.plan(A, E, D)
+    send_want, expert_want = oracle.dispatch(want, x)     # the oracle itself goes hop by hop
+    L = fusco.Layout(N, k, E, D)
+    fusco.fusco_plan(L, dev(A))
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    sb = torch.full((L.send_cap, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_dispatch(L, dev(x), eb, send_buf=sb, flags=fusco.DISPATCH_TWO_HOP)
+    torch.cuda.synchronize()
+    assert np.array_equal(eb.cpu().numpy(), expert_want)
+    assert np.array_equal(sb[:want.U].cpu().numpy(), send_want)
+    assert bool((sb[want.U:] == 0xEE).all())
+
+
+def test_two_hop_with_aux_plane_on_decode_config(fusco, oracle):
+    cfg = W.get_config("decode_fp8")
+    A, _ = W.make_routing(cfg)
+    q, sc = W.make_fp8_activations(cfg)
+    want = oracle.plan(A, cfg.E, cfg.D)
+    send_want, expert_want, saux_want, eaux_want = oracle.dispatch(want, q, sc)
+    L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+    fusco.fusco_plan(L, dev(A))
+    eb = torch.zeros((L.P, cfg.H), dtype=torch.uint8, device="cuda")
+    ea = torch.zeros((L.P, cfg.H // 128), dtype=torch.float32, device="cuda")
+    sb = torch.zeros((L.send_cap, cfg.H), dtype=torch.uint8, device="cuda")
+    sa = torch.zeros((L.send_cap, cfg.H // 128), dtype=torch.float32, device="cuda")
+    fusco.fusco_dispatch(L, dev(q), eb, x_aux=dev(sc), expert_aux=ea, send_buf=sb, send_aux=sa,
+                         flags=fusco.DISPATCH_TWO_HOP)
+    torch.cuda.synchronize()
+    assert np.array_equal(eb.cpu().numpy(), expert_want) and np.array_equal(ea.cpu().numpy(), eaux_want)
+    assert np.array_equal(sb[:want.U].cpu().numpy(), send_want) and np.array_equal(sa[:want.U].cpu().numpy(), saux_want)
+
+
+def test_two_hop_skips_invalid_pairs(fusco):
+    rng = np.random.default_rng(5)
+    N, k, E, D = 300, 4, 16, 4
+    A = random_topk(rng, N, k, E)
+    A[7, 2] = 99
+    A[200, 0] = -1
+    L = fusco.Layout(N, k, E, D)
+    fusco.fusco_plan(L, dev(A))
+    x = dev(rng.integers(0, 256, size=(N, 64), dtype=np.uint8))
+    eb = torch.full((L.P, 64), 0xEE, dtype=torch.uint8, device="cuda")
+    sb = torch.full((L.send_cap, 64), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_dispatch(L, x, eb, send_buf=sb, flags=fusco.DISPATCH_TWO_HOP)
+    torch.cuda.synchronize()
+    got = L.to_host()
+    assert int(got.status[0]) == 2
+    assigned = int(got.exp_off[E])
+    assert assigned == N * k - 2
+    assert torch.equal(eb[:assigned], x[dev(got.slot_token[:assigned]).long()])
+    assert bool((eb[assigned:] == 0xEE).all())
+
+
+@pytest.mark.parametrize("N,k,E,D,H", [(50, 2, 8, 4, 8), (300, 8, 256, 8, 7168), (513, 4, 16, 4, 296),
+                                       (129, 8, 64, 64, 1024), (90, 3, 6, 1, 512)])
+def test_disaggregated_baseline_matches_oracle(fusco, oracle, N, k, E, D, H):
+    rng = np.random.default_rng(N * H + 3)
+    A = random_topk(rng, N, k, E)
+    xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
+    w = rng.random((N, k)).astype(np.float32)
+    w /= w.sum(1, keepdims=True)
+    want = oracle.plan(A, E, D)
+    _, expert_want = oracle.dispatch(want, xb)
+    L = fusco.Layout(N, k, E, D)
+    Lr = fusco.Layout(N, k, D, D)
+    d_A = dev(A)
+    fusco.fusco_plan(L, d_A)
+    fusco.fusco_disaggregated_plan(Lr, L, d_A, torch.empty_like(d_A))
+    P = N * k
+    sa = torch.zeros((P, H), dtype=torch.bfloat16, device="cuda")
+    sb = torch.zeros((P, H), dtype=torch.bfloat16, device="cuda")
+    eb = torch.zeros((P, H), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_disaggregated_dispatch(L, Lr, bf16_dev(xb), sa, sb, eb)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_host(eb), expert_want)
+    # stage 1 of the paper's baseline: tokens rearranged by destination device (stable in (t, j))
+    dev_of_pair = (A // (E // D)).reshape(-1)
+    order = np.argsort(dev_of_pair, kind="stable")
+    assert np.array_equal(bits_host(sa), xb[order // k])
+    assert np.array_equal(bits_host(sb), xb[order // k])
+    # the rank-major plan is the oracle's plan of the device ids
+    rank_want = oracle.plan(A // (E // D), D, D)
+    got = Lr.to_host()
+    assert np.array_equal(got.pair_slot, rank_want.pair_slot) and np.array_equal(got.slot_token, rank_want.slot_token)
+
+    yb = W.bf16_bits(rng.standard_normal((P, H)).astype(np.float32))
+    o32, o16 = oracle.combine_f32(yb, w, want.pair_slot)
+    for out_dtype in (torch.bfloat16, torch.float32):
+        out = torch.full((N, H), float("nan"), dtype=out_dtype, device="cuda")
+        fusco.fusco_disaggregated_combine(L, Lr, bf16_dev(yb), dev(w), sa, sb, out)
+        torch.cuda.synchronize()
+        if out_dtype == torch.bfloat16:
+            assert np.array_equal(bits_host(out), o16)
+        else:
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), o32.view(np.uint32))
+        # stage 3' put every expert row at its rank row
+        assert np.array_equal(bits_host(sa), yb[want.pair_slot[order]])
