@@ -41,7 +41,8 @@ def _load():
         _lib = ctypes.CDLL(build())
         for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_dispatch_rows",
                      "fusco_oracle_combine_f64",
-                     "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64"):
+                     "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64",
+                     "fusco_oracle_combine_two_hop_f32"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -193,3 +194,21 @@ def combine_f32(y: np.ndarray, w: np.ndarray, pair_slot: np.ndarray, tokens=None
     if rc != 0:
         raise ValueError("fusco_oracle_combine_f32 failed with code %d" % rc)
     return o32, o16
+
+
+def combine_two_hop_f32(pl: Plan, y: np.ndarray, w: np.ndarray, tokens=None, want_partial: bool = False):
+    """Combine along the two levels in reverse (per-device partial sums, then their sum).
+    Returns (float32 [rows,H], bfloat16 bits [rows,H]) and, with want_partial, also the [U,H] partial rows."""
+    y, dt = _y_args(y)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    N, k = w.shape
+    tok, nt, rows = _tok_args(tokens, N)
+    H = y.shape[1]
+    o32 = np.empty((rows, H), dtype=np.float32)
+    o16 = np.empty((rows, H), dtype=np.uint16)
+    part = np.full((pl.U, H), np.nan, dtype=np.float32) if want_partial else None
+    rc = _load().fusco_oracle_combine_two_hop_f32(_p(y), dt, _p(w), _p(pl.pair_slot), _p(pl.pair_send_row),
+                                                  _p(pl.pair_first), N, k, H, _p(tok), nt, _p(part), _p(o32), _p(o16))
+    if rc != 0:
+        raise ValueError("fusco_oracle_combine_two_hop_f32 failed with code %d" % rc)
+    return (o32, o16, part) if want_partial else (o32, o16)

@@ -319,3 +319,53 @@ int fusco_oracle_combine_abs_f64(const void *y, int y_dtype, const float *w, con
     }
     return ORACLE_OK;
 }
+
+/*
+ * Combine along the two descriptor levels in reverse (the "symmetric reverse" of the two-hop
+ * dispatch; the paper gives no arithmetic for it, this is the reading used here):
+ *   level 2 reversed: every send row r = (token t, device d) receives the partial sum of the
+ *     token's entries on that device, partial[r] = sum_{j : dev(A[t][j]) = d} w[t][j] * y[slot(t,j)],
+ *     one fused multiply-add per term in ascending j starting from +0 (single precision);
+ *   level 1 reversed: out[t] = sum of the token's partial rows, plain single-precision additions
+ *     starting from +0 in the order in which the devices first appear among the token's entries.
+ * Only the association of the sum differs from fusco_oracle_combine_f32.
+ * partial (optional, [U][H] floats) receives the level-2 result for all send rows when tokens == NULL.
+ */
+int fusco_oracle_combine_two_hop_f32(const void *y, int y_dtype, const float *w, const int32_t *pair_slot,
+                                     const int32_t *pair_send_row, const uint8_t *pair_first,
+                                     int32_t T, int32_t K, int32_t H,
+                                     const int32_t *tokens, int32_t n_tokens,
+                                     float *partial, float *out_f32, uint16_t *out_bf16)
+{
+    if (!y || !w || !pair_slot || !pair_send_row || !pair_first || K <= 0 || H <= 0) return ORACLE_ERR_ARG;
+    if (y_dtype != ORACLE_BF16 && y_dtype != ORACLE_F32) return ORACLE_ERR_ARG;
+    if (partial && tokens) return ORACLE_ERR_ARG;
+    const int32_t rows = tokens ? n_tokens : T;
+    float *part = (float *)malloc((size_t)K * sizeof(float));   /* partial sums of one token, one column */
+    if (!part) return ORACLE_ERR_MEM;
+    for (int32_t i = 0; i < rows; ++i) {
+        const int32_t t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) { free(part); return ORACLE_ERR_ARG; }
+        const int64_t p0 = (int64_t)t * K;
+        for (int32_t c = 0; c < H; ++c) {
+            /* level 2 reversed: one partial per first appearance f, over the entries that share its send row */
+            for (int32_t f = 0; f < K; ++f) {
+                if (!pair_first[p0 + f]) continue;
+                float acc = 0.0f;
+                for (int32_t j = 0; j < K; ++j)
+                    if (pair_send_row[p0 + j] == pair_send_row[p0 + f])
+                        acc = fmaf(w[p0 + j], y_at(y, y_dtype, (int64_t)pair_slot[p0 + j] * H + c), acc);
+                part[f] = acc;
+                if (partial) partial[(int64_t)pair_send_row[p0 + f] * H + c] = acc;
+            }
+            /* level 1 reversed */
+            float acc = 0.0f;
+            for (int32_t f = 0; f < K; ++f)
+                if (pair_first[p0 + f]) acc = acc + part[f];
+            if (out_f32) out_f32[(int64_t)i * H + c] = acc;
+            if (out_bf16) out_bf16[(int64_t)i * H + c] = float_to_bf16(acc);
+        }
+    }
+    free(part);
+    return ORACLE_OK;
+}

@@ -170,3 +170,87 @@ def test_bf16_rounding_ties_to_even(oracle):
     w = np.ones((1, 1), dtype=np.float32)
     _, o16 = oracle.combine_f32(y, w, np.zeros(1, dtype=np.int32))
     assert o16.tolist() == [[0x3F80, 0x3F82, 0x3F81, 0xBF80]]
+
+
+# ---- combine along the two levels in reverse (per-device partial sums) ----
+
+def test_two_hop_combine_single_device_equals_flat_sum(oracle):
+    # D = 1: one partial per token holds the whole chain, so both associations coincide bit for bit
+    rng = np.random.default_rng(60)
+    N, k, E, H = 40, 8, 32, 24
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, 1)
+    y = _rand_bf16(rng, (pl.P, H))
+    w = rng.random((N, k)).astype(np.float32)
+    f32, b16 = oracle.combine_f32(y, w, pl.pair_slot)
+    h32, h16 = oracle.combine_two_hop_f32(pl, y, w)
+    assert np.array_equal(f32.view(np.uint32), h32.view(np.uint32)) and np.array_equal(b16, h16)
+
+
+def test_two_hop_combine_one_expert_per_device_is_products_then_ordered_adds(oracle):
+    # D = E: every partial is one correctly rounded product; the result is their float32 sum in j order
+    rng = np.random.default_rng(61)
+    N, k, E, H = 30, 5, 8, 16
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, E)
+    y = rng.standard_normal((pl.P, H)).astype(np.float32)
+    w = rng.standard_normal((N, k)).astype(np.float32)
+    h32, _, part = oracle.combine_two_hop_f32(pl, y, w, want_partial=True)
+    prod = w.reshape(N, k, 1) * y[pl.pair_slot].reshape(N, k, H)            # float32 multiply, rounded once
+    assert np.array_equal(part[pl.pair_send_row].reshape(N, k, H).view(np.uint32), prod.view(np.uint32))
+    acc = np.zeros((N, H), dtype=np.float32)
+    for j in range(k):
+        acc = acc + prod[:, j]
+    assert np.array_equal(h32.view(np.uint32), acc.view(np.uint32))
+
+
+def test_two_hop_combine_groups_by_device_in_first_appearance_order(oracle):
+    # hand case: devices of the entries are [1, 0, 1]; partials are (e0 + e2) and (e1); out = p(dev1) + p(dev0)
+    A = np.array([[2, 0, 3]], dtype=np.int32)
+    pl = oracle.plan(A, 4, 2)
+    assert pl.pair_first.tolist() == [1, 1, 0]
+    big, tiny = np.float32(2.0 ** 24), np.float32(1.0)
+    y = np.zeros((3, 1), dtype=np.float32)
+    y[pl.pair_slot[0]], y[pl.pair_slot[1]], y[pl.pair_slot[2]] = big, tiny, -big
+    w = np.ones((1, 3), dtype=np.float32)
+    h32, _, part = oracle.combine_two_hop_f32(pl, y, w, want_partial=True)
+    f32, _ = oracle.combine_f32(y, w, pl.pair_slot)
+    assert part[pl.pair_send_row[0], 0] == 0.0 and part[pl.pair_send_row[1], 0] == 1.0
+    assert h32[0, 0] == 1.0          # (2^24 - 2^24) + 1
+    assert f32[0, 0] == 0.0          # ((2^24 + 1) - 2^24) loses the 1 in single precision
+
+
+@pytest.mark.parametrize("k", [1, 2, 4, 8])
+def test_two_hop_combine_dyadic_weights_return_x_exactly(oracle, k):
+    rng = np.random.default_rng(62 + k)
+    N, E, D, H = 45, 16, 4, 32
+    A = random_topk(rng, N, k, E)
+    x = _rand_bf16(rng, (N, H))
+    pl = oracle.plan(A, E, D)
+    _, y = oracle.dispatch(pl, x)
+    w = np.full((N, k), 1.0 / k, dtype=np.float32)
+    h32, h16 = oracle.combine_two_hop_f32(pl, y, w)
+    assert np.array_equal(h16, x) and np.array_equal(h32, W.bf16_bits_to_f32(x))
+
+
+def test_two_hop_combine_error_bound_and_subset(oracle):
+    rng = np.random.default_rng(63)
+    N, k, E, D, H = 100, 8, 64, 8, 48
+    A = random_topk(rng, N, k, E)
+    pl = oracle.plan(A, E, D)
+    y = _rand_bf16(rng, (pl.P, H))
+    w = (rng.standard_normal((N, k)) * 2).astype(np.float32)
+    h32, h16, part = oracle.combine_two_hop_f32(pl, y, w, want_partial=True)
+    ref = oracle.combine_f64(y, w, pl.pair_slot)
+    scale = oracle.combine_abs_f64(y, w, pl.pair_slot)
+    assert np.all(np.abs(h32.astype(np.float64) - ref) <= (k + D) * 2.0 ** -24 * scale)
+    assert not np.isnan(part).any()
+    # every partial row is the flat sum of the token's entries on that device
+    for r in rng.integers(0, pl.U, size=40):
+        t = pl.send_src[r]
+        js = [j for j in range(k) if pl.pair_send_row[t * k + j] == r]
+        sub32, _ = oracle.combine_f32(y[pl.pair_slot[t * k + np.array(js)]], w[t:t + 1, js], np.arange(len(js), dtype=np.int32))
+        assert np.array_equal(part[r].view(np.uint32), sub32[0].view(np.uint32))
+    toks = np.array([99, 0, 5], dtype=np.int32)
+    s32, s16 = oracle.combine_two_hop_f32(pl, y, w, tokens=toks)
+    assert np.array_equal(s32, h32[toks]) and np.array_equal(s16, h16[toks])
