@@ -68,6 +68,10 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     two_hop = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=fusco.DISPATCH_TWO_HOP))
     wire = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=3))
     del d_send
+    d_part = torch.empty((L.send_cap, cfg.H), dtype=torch.float32, device="cuda")
+    two_hop_c = mean_ms(lambda: fusco.fusco_combine_two_hop(L, d_expert, d_w, d_part, d_out))
+    del d_part
+    U = int(L.array("send_off")[cfg.D].item())
     Lr = fusco.Layout(cfg.N, cfg.k, cfg.D, cfg.D)
     d_dev = torch.empty_like(d_A)
     rank_plan = mean_ms(lambda: fusco.fusco_disaggregated_plan(Lr, L, d_A, d_dev))
@@ -75,7 +79,9 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     st_b = torch.empty_like(d_expert)
     dis_d = mean_ms(lambda: fusco.fusco_disaggregated_dispatch(L, Lr, d_x, st_a, st_b, d_expert))
     dis_c = mean_ms(lambda: fusco.fusco_disaggregated_combine(L, Lr, d_expert, d_w, st_a, st_b, d_out))
-    return {"two_hop_dispatch_ms": two_hop, "fused_dispatch_with_wire_tensor_ms": wire,
+    return {"wire_rows_deduplicated": U, "wire_rows_one_per_pair": cfg.P, "wire_rows_ratio": U / cfg.P,
+            "two_hop_dispatch_ms": two_hop, "two_hop_combine_ms": two_hop_c,
+            "fused_dispatch_with_wire_tensor_ms": wire,
             "disaggregated_plan_extra_ms": rank_plan, "disaggregated_dispatch_ms": dis_d,
             "disaggregated_combine_ms": dis_c, "reps": reps}
 

@@ -145,6 +145,21 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
                   int out_dtype, int32_t H, uint32_t flags, void *stream);
 
 /*
+ * Combine along the two descriptor levels in reverse (mirror of FUSCO_DISPATCH_TWO_HOP; the paper
+ * only says the reverse path is symmetric, the arithmetic is this library's reading):
+ *   partial[r, :] = sum over the entries j of token send_src[r] whose send row is r of
+ *                   w[t, j] * y[pair_slot[t*k+j], :]      fp32 fused multiply-adds, ascending j, from +0
+ *   out[t, :]     = sum of the token's partial rows        fp32 additions from +0, in the order in which
+ *                                                          the devices first appear among the k entries
+ * so one fp32 row per (token, device) would cross the link instead of one row per (token, expert).
+ * d_partial: [send_cap, H] fp32 scratch tensor, rows < U are overwritten.  H must be a multiple of 4
+ * (and H * sizeof(y element) a multiple of 16).  The result differs from fusco_combine only by the
+ * association of the sum: at most (k + D) * 2^-24 * sum_j |w_j y_j| from the exact value.
+ */
+int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, float *d_partial,
+                          void *d_out, int out_dtype, int32_t H, void *stream);
+
+/*
  * Disaggregated baseline: the multi-stage shuffle the paper starts from (section 1: rearrange by
  * destination rank, all-to-all, rearrange by expert, and the symmetric reverse; section 5.4, the
  * "dComm-off" ablation, performs the rearrangements explicitly around the transfer).  Each stage is

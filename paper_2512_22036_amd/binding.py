@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
            "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy",
-           "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
+           "fusco_combine_two_hop", "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
 
 class FuscoError(RuntimeError):
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
     lp = ctypes.POINTER(_CLayout)
+    lib.fusco_combine_two_hop.restype = ctypes.c_int
+    lib.fusco_combine_two_hop.argtypes = [lp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, i32, vp]
     lib.fusco_disaggregated_plan.restype = ctypes.c_int
     lib.fusco_disaggregated_plan.argtypes = [lp, lp, vp, vp, vp, sz, vp]
     lib.fusco_disaggregated_dispatch.restype = ctypes.c_int
@@ -215,6 +217,25 @@ def fusco_combine(layout: Layout, y: torch.Tensor, w: torch.Tensor, out: torch.T
     _check(load_library().fusco_combine(ctypes.byref(layout.c), y.data_ptr(), _dtype_code(y, "y"), w.data_ptr(),
                                         out.data_ptr(), _dtype_code(out, "out"), H, 0, _stream(stream)),
            "fusco_combine")
+
+
+def fusco_combine_two_hop(layout: Layout, y: torch.Tensor, w: torch.Tensor, partial: torch.Tensor,
+                          out: torch.Tensor, stream=None) -> None:
+    _rows(y, "y", layout.P)
+    H = y.shape[1]
+    _rows(out, "out", layout.N)
+    _rows(partial, "partial", layout.send_cap, 4 * H)
+    if partial.dtype != torch.float32:
+        raise FuscoError("partial must be float32")
+    if out.shape[1] != H or H % 4 != 0:
+        raise FuscoError("out must have %d columns and H must be a multiple of 4" % H)
+    if (not w.is_cuda or w.dtype != torch.float32 or not w.is_contiguous()
+            or tuple(w.shape) != (layout.N, layout.k)):
+        raise FuscoError("w must be a contiguous float32 device tensor of shape [N, k]")
+    _check(load_library().fusco_combine_two_hop(ctypes.byref(layout.c), y.data_ptr(), _dtype_code(y, "y"),
+                                                w.data_ptr(), partial.data_ptr(), out.data_ptr(),
+                                                _dtype_code(out, "out"), H, _stream(stream)),
+           "fusco_combine_two_hop")
 
 
 def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -449,6 +449,8 @@ struct CombineArgs {
     const int32_t *pair_slot;
     int32_t k;
     int32_t C;   // 16-byte chunks per y row
+    // per-send-row mode (level 2 reversed): one workgroup per send row, only the token's entries on that row
+    const int32_t *pair_send_row, *send_src, *n_rows_dev;
 };
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
@@ -462,13 +464,18 @@ __device__ __forceinline__ uint32_t to_bf16(float f)
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
-template <bool Y_BF16, bool OUT_BF16, int CPT, int JU>
+template <bool Y_BF16, bool OUT_BF16, int CPT, int JU, bool PER_SEND_ROW = false>
 __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
 {
     constexpr int EPC = Y_BF16 ? 8 : 4;   // elements per 16-byte chunk of y
-    // last token first: when combine follows dispatch, the rows written last are the ones still in
+    // last row first: when combine follows dispatch, the rows written last are the ones still in
     // the memory-side cache
-    const int t = gridDim.x - 1 - blockIdx.x;
+    const int r = gridDim.x - 1 - blockIdx.x;   // token, or send row in the per-send-row mode
+    int t = r;
+    if constexpr (PER_SEND_ROW) {
+        if (r >= *a.n_rows_dev) return;
+        t = a.send_src[r];
+    }
     const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     const float *wt = a.w + (size_t)t * a.k;
@@ -490,7 +497,9 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
             if (j < a.k) {
                 const int slot = slots[j];
                 wj[jj] = wt[j];
-                if (slot >= 0) {
+                bool take = slot >= 0;
+                if constexpr (PER_SEND_ROW) take = take && a.pair_send_row[(size_t)t * a.k + j] == r;
+                if (take) {
                     on[jj] = true;
 #pragma unroll
                     for (int i = 0; i < CPT; ++i) {
@@ -524,7 +533,7 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
     for (int i = 0; i < CPT; ++i) {
         const int c = c0 + i * blockDim.x;
         if (c >= a.C) continue;
-        const size_t e0 = ((size_t)t * a.C + c) * EPC;   // first output element of this chunk
+        const size_t e0 = ((size_t)r * a.C + c) * EPC;   // first output element of this chunk
         if constexpr (OUT_BF16) {
             uint32_t pk[EPC / 2];
 #pragma unroll
@@ -544,6 +553,52 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
                 store16_through((u32x4 *)((float *)a.out + e0) + h, o);
             }
         }
+    }
+}
+
+// Level 1 reversed: out[t] = sum of the token's partial rows (fp32, one per destination device),
+// plain additions from +0 in the order in which the devices first appear among the token's entries.
+struct SumPartialsArgs {
+    const u32x4 *partial;   // [send rows, C] chunks of 4 floats
+    void *out;
+    const int32_t *pair_send_row;
+    const uint8_t *pair_first;
+    int32_t k;
+    int32_t C;              // 16-byte chunks (4 floats) per partial row
+};
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(1024) void sum_partials_kernel(SumPartialsArgs a)
+{
+    const int t = gridDim.x - 1 - blockIdx.x;
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    const int32_t *rows = a.pair_send_row + (size_t)t * a.k;
+    const uint8_t *first = a.pair_first + (size_t)t * a.k;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int j0 = 0; j0 < a.k; j0 += 8) {
+        u32x4 v[8];
+        bool on[8];
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            const int j = j0 + jj;
+            on[jj] = j < a.k && first[j];
+            if (on[jj]) v[jj] = load16_stream(a.partial + (size_t)rows[j] * a.C + c);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            if (!on[jj]) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = acc[q] + __uint_as_float(v[jj][q]);
+        }
+    }
+    const size_t e0 = ((size_t)t * a.C + c) * 4;
+    if constexpr (OUT_BF16) {
+        u32x2 o = {to_bf16(acc[0]) | (to_bf16(acc[1]) << 16), to_bf16(acc[2]) | (to_bf16(acc[3]) << 16)};
+        store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
+    } else {
+        u32x4 o = {__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+        store16_through((u32x4 *)((float *)a.out + e0), o);
     }
 }
 
@@ -680,6 +735,7 @@ void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int
     a.out = d_out;
     a.pair_slot = pair_slot;
     a.k = k;
+    a.pair_send_row = nullptr; a.send_src = nullptr; a.n_rows_dev = nullptr;
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
     // one workgroup per token whenever the row fits 1024 threads
     int cpt = 1;
@@ -863,6 +919,42 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
     const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream);
+    return launch_status();
+}
+
+int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, float *d_partial,
+                          void *d_out, int out_dtype, int32_t H, void *stream)
+{
+    if (!layout_ok(L) || !d_partial || !aligned16(d_partial)) return FUSCO_ERR_INVALID_ARG;
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
+    if (rc != FUSCO_OK || L->N == 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    // level 2 reversed: fp32 partial row per send row
+    CombineArgs a;
+    a.y = (const u32x4 *)d_y;
+    a.w = d_w;
+    a.out = d_partial;
+    a.pair_slot = L->pair_slot;
+    a.k = L->k;
+    a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
+    a.pair_send_row = L->pair_send_row; a.send_src = L->send_src; a.n_rows_dev = L->send_off + L->D;
+    int threads = round_up(a.C, kWave);
+    if (threads > 1024) threads = 1024;
+    const dim3 grid((unsigned)L->send_cap, (unsigned)((a.C + threads - 1) / threads));
+    if (y_dtype == FUSCO_BF16) hipLaunchKernelGGL((combine_kernel<true, false, 1, 8, true>), grid, dim3(threads), 0, s, a);
+    else hipLaunchKernelGGL((combine_kernel<false, false, 1, 8, true>), grid, dim3(threads), 0, s, a);
+    // level 1 reversed: sum of the token's partial rows
+    SumPartialsArgs b;
+    b.partial = (const u32x4 *)d_partial;
+    b.out = d_out;
+    b.pair_send_row = L->pair_send_row; b.pair_first = L->pair_first;
+    b.k = L->k;
+    b.C = H / 4;
+    int th2 = round_up(b.C, kWave);
+    if (th2 > 1024) th2 = 1024;
+    const dim3 grid2((unsigned)L->N, (unsigned)((b.C + th2 - 1) / th2));
+    if (out_dtype == FUSCO_BF16) hipLaunchKernelGGL(sum_partials_kernel<true>, grid2, dim3(th2), 0, s, b);
+    else hipLaunchKernelGGL(sum_partials_kernel<false>, grid2, dim3(th2), 0, s, b);
     return launch_status();
 }
 

@@ -115,6 +115,13 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert c(buf, 0, buf, buf, 7, 64, 0, None) == -3
     assert c(buf, 0, buf, buf, 0, 64, 1, None) == -3          # flags must be 0
     assert c(buf + 8, 0, buf, buf, 0, 64, 0, None) == -1
+    # two-hop combine
+    th = lambda *a: lib.fusco_combine_two_hop(ctypes.byref(L), *a)
+    assert th(buf, 0, buf, None, buf, 0, 64, None) == -1          # no partial tensor
+    assert th(buf, 0, buf, buf + 4, buf, 0, 64, None) == -1       # misaligned partial tensor
+    assert th(None, 0, buf, buf, buf, 0, 64, None) == -1
+    assert th(buf, 0, buf, buf, buf, 5, 64, None) == -3
+    assert th(buf, 0, buf, buf, buf, 0, 20, None) == -1
     # disaggregated baseline
     Lr = _CLayout()
     assert lib.fusco_layout_bind(ctypes.byref(Lr), N, k, D, D, base + (1 << 24), lib.fusco_layout_bytes(N, k, D, D)) == 0

@@ -136,3 +136,57 @@ def test_disaggregated_baseline_matches_oracle(fusco, oracle, N, k, E, D, H):
             assert np.array_equal(out.cpu().numpy().view(np.uint32), o32.view(np.uint32))
         # stage 3' put every expert row at its rank row
         assert np.array_equal(bits_host(sa), yb[want.pair_slot[order]])
+
+
+TWO_HOP_COMBINE_SHAPES = [(50, 2, 8, 4, 8), (300, 8, 256, 8, 7168), (65, 4, 16, 4, 296), (129, 8, 64, 64, 1024),
+                          (90, 3, 6, 1, 512), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096)]
+
+
+@pytest.mark.parametrize("N,k,E,D,H", TWO_HOP_COMBINE_SHAPES)
+@pytest.mark.parametrize("y_f32", [False, True])
+def test_two_hop_combine_matches_oracle(fusco, oracle, N, k, E, D, H, y_f32):
+    rng = np.random.default_rng(N * H + k + 7)
+    A = random_topk(rng, N, k, E)
+    want = oracle.plan(A, E, D)
+    if y_f32:
+        y = rng.standard_normal((N * k, H)).astype(np.float32)
+        d_y = dev(y)
+    else:
+        y = W.bf16_bits(rng.standard_normal((N * k, H)).astype(np.float32))
+        d_y = bf16_dev(y)
+    w = (rng.standard_normal((N, k)) * 2).astype(np.float32)
+    o32, o16, part = oracle.combine_two_hop_f32(want, y, w, want_partial=True)
+    ref = oracle.combine_f64(y, w, want.pair_slot)
+    scale = oracle.combine_abs_f64(y, w, want.pair_slot)
+    L = fusco.Layout(N, k, E, D)
+    fusco.fusco_plan(L, dev(A))
+    for out_dtype in (torch.float32, torch.bfloat16):
+        d_p = torch.full((L.send_cap, H), float("nan"), dtype=torch.float32, device="cuda")
+        out = torch.full((N, H), float("nan"), dtype=out_dtype, device="cuda")
+        fusco.fusco_combine_two_hop(L, d_y, dev(w), d_p, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_p[:want.U].cpu().numpy().view(np.uint32), part.view(np.uint32))
+        assert bool(torch.isnan(d_p[want.U:]).all())        # rows past U stay untouched
+        if out_dtype == torch.float32:
+            g = out.cpu().numpy()
+            assert np.array_equal(g.view(np.uint32), o32.view(np.uint32))
+            assert np.all(np.abs(g.astype(np.float64) - ref) <= 1e-5 * scale)
+        else:
+            assert np.array_equal(bits_host(out), o16)
+
+
+def test_two_hop_round_trip_returns_input_exactly(fusco):
+    rng = np.random.default_rng(9)
+    N, k, E, D, H = 600, 8, 64, 8, 2048
+    A = random_topk(rng, N, k, E)
+    xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
+    L = fusco.Layout(N, k, E, D)
+    fusco.fusco_plan(L, dev(A))
+    eb = torch.empty((L.P, H), dtype=torch.bfloat16, device="cuda")
+    sb = torch.empty((L.send_cap, H), dtype=torch.bfloat16, device="cuda")
+    part = torch.empty((L.send_cap, H), dtype=torch.float32, device="cuda")
+    out = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_dispatch(L, bf16_dev(xb), eb, send_buf=sb, flags=fusco.DISPATCH_TWO_HOP)
+    fusco.fusco_combine_two_hop(L, eb, torch.full((N, k), 1.0 / k, device="cuda"), part, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_host(out), xb)
