@@ -187,6 +187,18 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
                                 int32_t H, void *stream);
 
 /*
+ * Online Group-Balanced Assignment (Algorithm 1, section 3.4).  Host-only, no GPU work.
+ * load: [nodes, gpus] row-major, cross-node traffic load of every GPU.  For every node the GPUs are
+ * sorted by descending load (equal loads keep ascending GPU index), the sorted list is rotated by
+ * the node index, and communication group i takes the GPU at position i of every node's rotated
+ * list: group_gpu[i * nodes + n] = sorted_n[(i + n) mod gpus], for gpus groups of one GPU per node.
+ * The direction of the rotation and the tie order are not fixed by the paper; these are this
+ * library's readings.  O(gpus^2) per node (gpus is 4..8 in practice).
+ * Errors: FUSCO_ERR_INVALID_ARG (null, sizes < 1 or nodes * gpus > 2^24), FUSCO_ERR_WORKSPACE (host allocation failed).
+ */
+int fusco_balance_groups(const int64_t *load, int32_t nodes, int32_t gpus, int32_t *group_gpu);
+
+/*
  * Measurement aid: plain device copy of `bytes` bytes (multiple of 16) with the same 16-byte
  * accesses the shuffle kernels use.  Used to calibrate hardware traffic counters and as the
  * copy ceiling next to the shuffle's bandwidth.

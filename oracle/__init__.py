@@ -212,3 +212,20 @@ def combine_two_hop_f32(pl: Plan, y: np.ndarray, w: np.ndarray, tokens=None, wan
     if rc != 0:
         raise ValueError("fusco_oracle_combine_two_hop_f32 failed with code %d" % rc)
     return (o32, o16, part) if want_partial else (o32, o16)
+
+
+def balance_groups(load) -> np.ndarray:
+    """Online Group-Balanced Assignment (Algorithm 1 of the paper), step by step in its notation.
+
+    load[n][g] is the cross-node traffic load of GPU g of node n.  Returns G with G[i][n] = the GPU of
+    node n that belongs to communication group g_i.  Readings where the algorithm is silent: equal
+    loads keep ascending GPU index; "circular shift by n" moves position n of P_n to the front."""
+    load = np.asarray(load)
+    nodes, gpus = load.shape
+    P = [sorted(range(gpus), key=lambda g, n=n: (-int(load[n][g]), g)) for n in range(nodes)]   # sort by descending load
+    S = [P[n][n % gpus:] + P[n][:n % gpus] for n in range(nodes)]                              # circular shift by n
+    G = np.empty((gpus, nodes), dtype=np.int32)
+    for i in range(gpus):                                                                       # form groups
+        for n in range(nodes):
+            G[i][n] = S[n][i]
+    return G

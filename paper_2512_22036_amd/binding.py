@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
            "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy",
-           "fusco_combine_two_hop", "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
+           "fusco_combine_two_hop", "fusco_balance_groups", "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
 
 class FuscoError(RuntimeError):
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
     lp = ctypes.POINTER(_CLayout)
+    lib.fusco_balance_groups.restype = ctypes.c_int
+    lib.fusco_balance_groups.argtypes = [vp, i32, i32, vp]
     lib.fusco_combine_two_hop.restype = ctypes.c_int
     lib.fusco_combine_two_hop.argtypes = [lp, vp, ctypes.c_int, vp, vp, vp, ctypes.c_int, i32, vp]
     lib.fusco_disaggregated_plan.restype = ctypes.c_int
@@ -236,6 +238,18 @@ def fusco_combine_two_hop(layout: Layout, y: torch.Tensor, w: torch.Tensor, part
                                                 w.data_ptr(), partial.data_ptr(), out.data_ptr(),
                                                 _dtype_code(out, "out"), H, _stream(stream)),
            "fusco_combine_two_hop")
+
+
+def fusco_balance_groups(load) -> "numpy.ndarray":
+    """Algorithm 1 on a host [nodes, gpus] int64 load matrix; returns group_gpu [gpus, nodes] int32."""
+    import numpy as np
+    load = np.ascontiguousarray(load, dtype=np.int64)
+    if load.ndim != 2:
+        raise FuscoError("load must be a [nodes, gpus] matrix")
+    nodes, gpus = load.shape
+    out = np.empty((gpus, nodes), dtype=np.int32)
+    _check(load_library().fusco_balance_groups(load.ctypes.data, nodes, gpus, out.ctypes.data), "fusco_balance_groups")
+    return out
 
 
 def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

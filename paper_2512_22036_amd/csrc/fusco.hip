@@ -1013,6 +1013,29 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
     return launch_status();
 }
 
+int fusco_balance_groups(const int64_t *load, int32_t nodes, int32_t gpus, int32_t *group_gpu)
+{
+    if (!load || !group_gpu || nodes < 1 || gpus < 1 || (int64_t)nodes * gpus > (1 << 24)) return FUSCO_ERR_INVALID_ARG;
+    int32_t *perm = (int32_t *)malloc((size_t)gpus * sizeof(int32_t));
+    if (!perm) return FUSCO_ERR_WORKSPACE;
+    for (int32_t n = 0; n < nodes; ++n) {
+        const int64_t *l = load + (size_t)n * gpus;
+        // P_n: local GPUs by descending load (insertion sort, stable: equal loads keep index order)
+        for (int32_t g = 0; g < gpus; ++g) {
+            int32_t pos = g;
+            while (pos > 0 && l[perm[pos - 1]] < l[g]) {
+                perm[pos] = perm[pos - 1];
+                --pos;
+            }
+            perm[pos] = g;
+        }
+        // S_n: P_n rotated by the node index; group i takes position i of S_n
+        for (int32_t i = 0; i < gpus; ++i) group_gpu[(size_t)i * nodes + n] = perm[(i + n) % gpus];
+    }
+    free(perm);
+    return FUSCO_OK;
+}
+
 int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream)
 {
     if (!d_dst || !d_src || bytes % 16 != 0 || !aligned16(d_dst) || !aligned16(d_src)) return FUSCO_ERR_INVALID_ARG;
