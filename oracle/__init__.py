@@ -42,7 +42,7 @@ def _load():
         for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_dispatch_rows",
                      "fusco_oracle_combine_f64",
                      "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64",
-                     "fusco_oracle_combine_two_hop_f32"):
+                     "fusco_oracle_combine_two_hop_f32", "fusco_oracle_segments_copy"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -229,3 +229,22 @@ def balance_groups(load) -> np.ndarray:
         for n in range(nodes):
             G[i][n] = S[n][i]
     return G
+
+
+def segments_copy(src: np.ndarray, size, src_off=None, dst_off=None, dst_bytes: Optional[int] = None,
+                  slice_bytes: int = 0, fill_value: int = 0):
+    """Move n segments from src (uint8) into a new uint8 buffer of dst_bytes (default: total size).
+    src_off / dst_off None means that side is the contiguous stream.  Returns dst, or (dst, slice_fill)
+    when slice_bytes > 0."""
+    src = np.ascontiguousarray(src, dtype=np.uint8)
+    size = np.ascontiguousarray(size, dtype=np.uint64)
+    so = None if src_off is None else np.ascontiguousarray(src_off, dtype=np.uint64)
+    do = None if dst_off is None else np.ascontiguousarray(dst_off, dtype=np.uint64)
+    total = int(size.sum())
+    dst = np.full(total if dst_bytes is None else dst_bytes, fill_value, dtype=np.uint8)
+    fill = np.zeros((total + slice_bytes - 1) // slice_bytes, dtype=np.uint32) if slice_bytes > 0 else None
+    rc = _load().fusco_oracle_segments_copy(_p(src), _p(so), _p(dst), _p(do), _p(size), ctypes.c_int64(len(size)),
+                                            ctypes.c_uint64(slice_bytes), _p(fill))
+    if rc != 0:
+        raise ValueError("fusco_oracle_segments_copy failed with code %d" % rc)
+    return (dst, fill) if slice_bytes > 0 else dst

@@ -369,3 +369,34 @@ int fusco_oracle_combine_two_hop_f32(const void *y, int y_dtype, const float *w,
     free(part);
     return ORACLE_OK;
 }
+
+/*
+ * Segment-descriptor transfer (section "Data-Fused Communication Engine", paragraph "Segment
+ * descriptor"): a payload is a sequence of n logical segments; segment i is size[i] bytes long and
+ * lies at src_off[i] in the sender's memory and at dst_off[i] in the receiver's.  The descriptor
+ * lists are dense arrays in transfer order and map one to one.  A NULL offset list means that side
+ * is the contiguous stream itself (segment i starts at the cumulative size of the segments before
+ * it), which is how segments are bundled into slices for the network.
+ * slice_fill (optional, with slice_bytes > 0): bytes of the contiguous stream that fall into every
+ * slice of slice_bytes, i.e. what a consumer waits for before it takes the slice.
+ */
+int fusco_oracle_segments_copy(const uint8_t *src, const uint64_t *src_off, uint8_t *dst, const uint64_t *dst_off,
+                               const uint64_t *size, int64_t n, uint64_t slice_bytes, uint32_t *slice_fill)
+{
+    if (!src || !dst || !size || n < 0) return ORACLE_ERR_ARG;
+    uint64_t cum = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const uint64_t so = src_off ? src_off[i] : cum;
+        const uint64_t dofs = dst_off ? dst_off[i] : cum;
+        memcpy(dst + dofs, src + so, (size_t)size[i]);
+        cum += size[i];
+    }
+    if (slice_fill && slice_bytes > 0) {
+        const uint64_t slices = (cum + slice_bytes - 1) / slice_bytes;
+        for (uint64_t s = 0; s < slices; ++s) {
+            const uint64_t left = cum - s * slice_bytes;
+            slice_fill[s] = (uint32_t)(left < slice_bytes ? left : slice_bytes);
+        }
+    }
+    return ORACLE_OK;
+}
