@@ -72,6 +72,22 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     two_hop_c = mean_ms(lambda: fusco.fusco_combine_two_hop(L, d_expert, d_w, d_part, d_out))
     del d_part
     U = int(L.array("send_off")[cfg.D].item())
+    # segment-descriptor engine on the same rows: the level-1 transfer written as (offset, size) descriptors,
+    # packed into one contiguous stream cut into 1 MiB slices
+    row = cfg.row_bytes
+    src_tok = L.array("send_src")[:U].to(torch.int64)
+    desc = torch.stack([src_tok * row, torch.full_like(src_tok, row)], dim=1).contiguous()
+    cum = torch.empty(U + 1, dtype=torch.int64, device="cuda")
+    seg_status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cap = U * row
+    stream_buf = torch.empty(cap, dtype=torch.uint8, device="cuda")
+    fill = torch.empty((cap + (1 << 20) - 1) >> 20, dtype=torch.int32, device="cuda")
+    seg_scan = mean_ms(lambda: fusco.fusco_segments_scan(desc, cum, seg_status))
+    seg_pack = mean_ms(lambda: fusco.fusco_segments_copy(d_x, desc, stream_buf, None, cum, cap, seg_status,
+                                                         slice_bytes=1 << 20, slice_fill=fill))
+    seg_ok = int(seg_status.item()) == 0 and int(fill.sum().item()) == cap
+    seg_pack_plain = mean_ms(lambda: fusco.fusco_segments_copy(d_x, desc, stream_buf, None, cum, cap, seg_status))
+    del stream_buf, desc, cum, fill
     Lr = fusco.Layout(cfg.N, cfg.k, cfg.D, cfg.D)
     d_dev = torch.empty_like(d_A)
     rank_plan = mean_ms(lambda: fusco.fusco_disaggregated_plan(Lr, L, d_A, d_dev))
@@ -82,6 +98,9 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     return {"wire_rows_deduplicated": U, "wire_rows_one_per_pair": cfg.P, "wire_rows_ratio": U / cfg.P,
             "two_hop_dispatch_ms": two_hop, "two_hop_combine_ms": two_hop_c,
             "fused_dispatch_with_wire_tensor_ms": wire,
+            "segments_scan_ms": seg_scan, "segments_pack_ms": seg_pack,
+            "segments_pack_GBps": 2.0 * cap / (seg_pack * 1e-3) / 1e9, "segments_ok": seg_ok,
+            "segments_pack_without_slices_ms": seg_pack_plain,
             "disaggregated_plan_extra_ms": rank_plan, "disaggregated_dispatch_ms": dis_d,
             "disaggregated_combine_ms": dis_c, "reps": reps}
 

@@ -199,6 +199,45 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
 int fusco_balance_groups(const int64_t *load, int32_t nodes, int32_t gpus, int32_t *group_gpu);
 
 /*
+ * Segment descriptor (section 3.2): where a logical segment lies, as a byte offset from a base
+ * pointer, and its size in bytes.  Offsets and sizes must be multiples of 16.  A descriptor list is
+ * a dense array in transfer order; the sender's and the receiver's lists map one to one.
+ */
+typedef struct fusco_segment {
+    uint64_t offset;
+    uint64_t size;
+} fusco_segment;
+
+/*
+ * Cumulative bytes of a descriptor list: d_cum[0] = 0, d_cum[i+1] = d_cum[i] + size of segment i
+ * (d_cum has n + 1 entries).  The engine finds the segment of a stream position from this array.
+ * Descriptors with an offset or size that is not a multiple of 16 are counted in *d_status and take
+ * part with size 0.  n <= 2^26.  One launch, one workgroup.
+ */
+int fusco_segments_scan(const fusco_segment *d_desc, int64_t n, uint64_t *d_cum, int32_t *d_status, void *stream);
+
+/*
+ * Descriptor-driven transfer of n segments (section 3.2): segment i is read at d_src + the
+ * sender's offset and written at d_dst + the receiver's offset; its size comes from d_cum (built
+ * by fusco_segments_scan from either list: the lists must agree on sizes).  A NULL descriptor list
+ * means that side is the contiguous stream, i.e. segment i starts at d_cum[i]: with d_dst_desc ==
+ * NULL the segments are gathered and packed into one buffer (sender side, slices for the network),
+ * with d_src_desc == NULL a packed buffer is scattered to its final places (receiver side).
+ * src_bytes / dst_bytes: sizes of the two buffers; a 16-byte unit that would fall outside, or is
+ * misaligned, is skipped and counted in *d_status (which this call only adds to: it continues the
+ * count of fusco_segments_scan).  stream_capacity: upper bound of the total size known on the
+ * host (the exact total is read on the device from d_cum[n]).
+ * Slices: if d_slice_fill is given, the contiguous stream is cut into slices of slice_bytes (a
+ * multiple of 16384) and d_slice_fill[s] counts the bytes of slice s that have been written and are
+ * visible; it is reset to 0 at the start of the call.  A consumer takes slice s once the count
+ * reaches min(slice_bytes, total - s * slice_bytes).
+ */
+int fusco_segments_copy(const void *d_src, uint64_t src_bytes, const fusco_segment *d_src_desc, void *d_dst,
+                        uint64_t dst_bytes, const fusco_segment *d_dst_desc, const uint64_t *d_cum, int64_t n,
+                        uint64_t stream_capacity, uint64_t slice_bytes, uint32_t *d_slice_fill, int32_t *d_status,
+                        void *stream);
+
+/*
  * Measurement aid: plain device copy of `bytes` bytes (multiple of 16) with the same 16-byte
  * accesses the shuffle kernels use.  Used to calibrate hardware traffic counters and as the
  * copy ceiling next to the shuffle's bandwidth.

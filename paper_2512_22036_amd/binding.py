@@ -22,7 +22,8 @@ _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
            "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy",
-           "fusco_combine_two_hop", "fusco_balance_groups", "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
+           "fusco_combine_two_hop", "fusco_balance_groups", "fusco_segments_scan", "fusco_segments_copy",
+           "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
 
 class FuscoError(RuntimeError):
@@ -77,6 +78,11 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
     lp = ctypes.POINTER(_CLayout)
+    u64, i64 = ctypes.c_uint64, ctypes.c_int64
+    lib.fusco_segments_scan.restype = ctypes.c_int
+    lib.fusco_segments_scan.argtypes = [vp, i64, vp, vp, vp]
+    lib.fusco_segments_copy.restype = ctypes.c_int
+    lib.fusco_segments_copy.argtypes = [vp, u64, vp, vp, u64, vp, vp, i64, u64, u64, vp, vp, vp]
     lib.fusco_balance_groups.restype = ctypes.c_int
     lib.fusco_balance_groups.argtypes = [vp, i32, i32, vp]
     lib.fusco_combine_two_hop.restype = ctypes.c_int
@@ -250,6 +256,56 @@ def fusco_balance_groups(load) -> "numpy.ndarray":
     out = np.empty((gpus, nodes), dtype=np.int32)
     _check(load_library().fusco_balance_groups(load.ctypes.data, nodes, gpus, out.ctypes.data), "fusco_balance_groups")
     return out
+
+
+def _desc_ok(desc: Optional[torch.Tensor], n: int, name: str) -> None:
+    if desc is None:
+        return
+    if not desc.is_cuda or desc.dtype != torch.int64 or not desc.is_contiguous() or tuple(desc.shape) != (n, 2):
+        raise FuscoError("%s must be a contiguous int64 device tensor of shape [n, 2] (offset, size)" % name)
+
+
+def fusco_segments_scan(desc: torch.Tensor, cum: torch.Tensor, status: torch.Tensor, stream=None) -> None:
+    """desc: int64 [n, 2] (offset, size) on the device; cum: int64 [n + 1]; status: int32 [1]."""
+    n = desc.shape[0]
+    _desc_ok(desc, n, "desc")
+    if not cum.is_cuda or cum.dtype != torch.int64 or not cum.is_contiguous() or cum.numel() != n + 1:
+        raise FuscoError("cum must be a contiguous int64 device tensor with n + 1 entries")
+    if not status.is_cuda or status.dtype != torch.int32 or status.numel() != 1:
+        raise FuscoError("status must be an int32 device tensor with one entry")
+    _check(load_library().fusco_segments_scan(desc.data_ptr(), n, cum.data_ptr(), status.data_ptr(), _stream(stream)),
+           "fusco_segments_scan")
+
+
+def fusco_segments_copy(src: torch.Tensor, src_desc: Optional[torch.Tensor], dst: torch.Tensor,
+                        dst_desc: Optional[torch.Tensor], cum: torch.Tensor, stream_capacity: int,
+                        status: torch.Tensor, slice_bytes: int = 0, slice_fill: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """src / dst: contiguous device tensors viewed as bytes; a None descriptor list means that side is the
+    contiguous stream.  slice_fill: int32 [ceil(stream_capacity / slice_bytes)] or None."""
+    n = cum.numel() - 1
+    _desc_ok(src_desc, n, "src_desc")
+    _desc_ok(dst_desc, n, "dst_desc")
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise FuscoError("src and dst must be contiguous device tensors")
+    if not cum.is_cuda or cum.dtype != torch.int64 or not cum.is_contiguous() or n < 0:
+        raise FuscoError("cum must be a contiguous int64 device tensor with n + 1 entries")
+    if not status.is_cuda or status.dtype != torch.int32 or status.numel() != 1:
+        raise FuscoError("status must be an int32 device tensor with one entry")
+    src_bytes, dst_bytes = src.numel() * src.element_size(), dst.numel() * dst.element_size()
+    if src_desc is None and src_bytes < stream_capacity or dst_desc is None and dst_bytes < stream_capacity:
+        raise FuscoError("the contiguous side is smaller than stream_capacity")
+    if slice_fill is not None:
+        if slice_bytes <= 0:
+            raise FuscoError("slice_bytes must be positive with slice_fill")
+        need = (stream_capacity + slice_bytes - 1) // slice_bytes
+        if (not slice_fill.is_cuda or slice_fill.dtype != torch.int32 or not slice_fill.is_contiguous()
+                or slice_fill.numel() < need):
+            raise FuscoError("slice_fill must be a contiguous int32 device tensor with %d entries" % need)
+    _check(load_library().fusco_segments_copy(src.data_ptr(), src_bytes, _ptr(src_desc), dst.data_ptr(), dst_bytes,
+                                              _ptr(dst_desc), cum.data_ptr(), n, stream_capacity, slice_bytes,
+                                              _ptr(slice_fill), status.data_ptr(), _stream(stream)),
+           "fusco_segments_copy")
 
 
 def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

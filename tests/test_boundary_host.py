@@ -122,6 +122,20 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert th(None, 0, buf, buf, buf, 0, 64, None) == -1
     assert th(buf, 0, buf, buf, buf, 5, 64, None) == -3
     assert th(buf, 0, buf, buf, buf, 0, 20, None) == -1
+    # segment engine
+    assert lib.fusco_segments_scan(None, 4, buf, buf, None) == -1
+    assert lib.fusco_segments_scan(buf, -1, buf, buf, None) == -1
+    assert lib.fusco_segments_scan(buf, 4, None, buf, None) == -1
+    assert lib.fusco_segments_scan(buf, 4, buf, None, None) == -1
+    assert lib.fusco_segments_scan(buf, 1 << 27, buf, buf, None) == -1
+    sc = lambda *a: lib.fusco_segments_copy(*a)
+    assert sc(None, 64, buf, buf, 64, None, buf, 1, 64, 0, None, buf, None) == -1
+    assert sc(buf, 64, buf, None, 64, None, buf, 1, 64, 0, None, buf, None) == -1
+    assert sc(buf, 64, buf, buf, 64, None, None, 1, 64, 0, None, buf, None) == -1
+    assert sc(buf, 64, buf, buf, 64, None, buf, 1, 64, 0, None, None, None) == -1
+    assert sc(buf + 8, 64, buf, buf, 64, None, buf, 1, 64, 0, None, buf, None) == -1
+    assert sc(buf, 64, buf, buf, 64, None, buf, 1, 64, 1000, buf, buf, None) == -1      # slice size not a multiple of 16384
+    assert sc(buf, 64, buf, buf, 64, None, buf, 1, 64, 0, buf, buf, None) == -1         # slice counters without a slice size
     # disaggregated baseline
     Lr = _CLayout()
     assert lib.fusco_layout_bind(ctypes.byref(Lr), N, k, D, D, base + (1 << 24), lib.fusco_layout_bytes(N, k, D, D)) == 0

@@ -1,0 +1,97 @@
+"""Segment-descriptor engine on the GPU against the oracle: pack, unpack, scatter to scatter, slice
+fill counters, invalid descriptors."""
+import numpy as np
+import pytest
+import torch
+
+from definitions import random_topk
+from test_oracle_segments import _random_layout
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fusco():
+    import paper_2512_22036_amd as f
+    f.load_library()
+    assert torch.cuda.is_available()
+    return f
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def desc_dev(off, size):
+    return dev(np.stack([np.asarray(off, dtype=np.int64), np.asarray(size, dtype=np.int64)], axis=1))
+
+
+def scan(fusco, desc):
+    n = desc.shape[0]
+    cum = torch.full((n + 1,), -1, dtype=torch.int64, device="cuda")
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    fusco.fusco_segments_scan(desc, cum, status)
+    return cum, status
+
+
+@pytest.mark.parametrize("n,max_units", [(0, 4), (1, 4), (7, 40), (300, 40), (5000, 9), (2000, 1200), (70000, 3)])
+def test_pack_and_unpack_match_oracle(fusco, oracle, n, max_units):
+    rng = np.random.default_rng(n + max_units)
+    size, off, span = _random_layout(rng, n, max_units=max_units)
+    src = rng.integers(0, 256, size=max(span, 16), dtype=np.uint8)
+    total = int(size.sum())
+    cap = total + 4096
+    want, fill_want = oracle.segments_copy(src, size, src_off=off, slice_bytes=16384) if n else (np.zeros(0, np.uint8), np.zeros(0, np.uint32))
+    d_desc = desc_dev(off, size) if n else torch.zeros((0, 2), dtype=torch.int64, device="cuda")
+    cum, status = scan(fusco, d_desc)
+    assert np.array_equal(cum.cpu().numpy(), np.concatenate([[0], np.cumsum(size.astype(np.int64))]))
+    packed = torch.full((cap,), 0xCD, dtype=torch.uint8, device="cuda")
+    fill = torch.full(((cap + 16383) // 16384,), 77, dtype=torch.int32, device="cuda")
+    fusco.fusco_segments_copy(dev(src), d_desc, packed, None, cum, cap, status, slice_bytes=16384, slice_fill=fill)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    assert np.array_equal(packed[:total].cpu().numpy(), want)
+    assert bool((packed[total:] == 0xCD).all())
+    got_fill = fill.cpu().numpy()
+    assert np.array_equal(got_fill[:len(fill_want)], fill_want.astype(np.int32)) and np.all(got_fill[len(fill_want):] == 0)
+    # receiver side: scatter the packed stream back
+    back = torch.full((max(span, 16),), 0xAB, dtype=torch.uint8, device="cuda")
+    fusco.fusco_segments_copy(packed, None, back, d_desc, cum, cap, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    if n:
+        want_back = oracle.segments_copy(want, size, dst_off=off, dst_bytes=len(src), fill_value=0xAB)
+        assert np.array_equal(back.cpu().numpy(), want_back)
+
+
+def test_scatter_to_scatter_and_token_rows(fusco, oracle):
+    # the shuffle's level 2 written as a descriptor list: one 14336-byte segment per slot
+    rng = np.random.default_rng(3)
+    N, k, E, D, row = 300, 8, 64, 8, 14336
+    A = random_topk(rng, N, k, E)
+    x = rng.integers(0, 256, size=(N, row), dtype=np.uint8)
+    pl = oracle.plan(A, E, D)
+    _, expert_want = oracle.dispatch(pl, x)
+    size = np.full(pl.P, row, dtype=np.int64)
+    src_desc = desc_dev(pl.slot_token.astype(np.int64) * row, size)
+    dst_desc = desc_dev(np.arange(pl.P, dtype=np.int64) * row, size)
+    cum, status = scan(fusco, src_desc)
+    out = torch.zeros((pl.P, row), dtype=torch.uint8, device="cuda")
+    fusco.fusco_segments_copy(dev(x), src_desc, out, dst_desc, cum, pl.P * row, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and np.array_equal(out.cpu().numpy(), expert_want)
+
+
+def test_invalid_descriptors_are_counted_and_skipped(fusco):
+    size = np.array([64, 40, 32, 64], dtype=np.int64)       # 40 is not a multiple of 16
+    off = np.array([0, 64, 136, 4096], dtype=np.int64)      # 136 is not a multiple of 16; 4096 lies outside src
+    d = desc_dev(off, size)
+    cum, status = scan(fusco, d)
+    assert int(status.item()) == 2
+    assert cum.cpu().tolist() == [0, 64, 64, 64, 128]
+    src = torch.arange(256, dtype=torch.uint8, device="cuda")
+    dst = torch.full((256,), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_segments_copy(src, d, dst, None, cum, 256, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 2 + 4                      # four 16-byte units of the out-of-range segment
+    assert torch.equal(dst[:64], src[:64]) and bool((dst[64:] == 0xEE).all())
