@@ -29,6 +29,7 @@ constexpr int kMaxBins = FUSCO_MAX_E;
 constexpr size_t kMaxRowChunks = 1u << 16;              // rows of at most 1 MiB
 
 static_assert(kTilePairs >= FUSCO_MAX_K, "a tile must hold at least one token");
+static_assert(kMaxBins <= kPlanThreads, "the planner gives every bin a thread");
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -194,6 +195,10 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
     const uint64_t lt = ((uint64_t)1 << lane) - 1;
 
     for (int b = lane; b < nb; b += kWave) s.wave_cnt[wave][b] = 0;
+    for (int b = tid; b < nb; b += kPlanThreads) {
+        s.total[b] = 0;
+        s.base[b] = 0;
+    }
     __syncthreads();
 
     // rank inside the wave's chunk; wave_cnt[wave][key] is the running count of the key
@@ -210,26 +215,36 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
     }
     __syncthreads();
 
-    // per key: total over all tiles and the part that lies in earlier tiles
-    for (int b = tid; b < nb; b += kPlanThreads) {
-        int tot = 0, pre = 0;
-        if constexpr (SINGLE) {
+    // per key: total over all tiles and the part that lies in earlier tiles.  The workgroup splits
+    // the tiles into as many interleaved parts as it has groups of nb threads, so that every
+    // thread keeps only a few independent loads in flight; partial sums meet in LDS.
+    if constexpr (SINGLE) {
+        for (int b = tid; b < nb; b += kPlanThreads) {
+            int tot = 0;
             for (int w = 0; w < kPlanWaves; ++w) tot += s.wave_cnt[w][b];
-        } else {
+            s.total[b] = tot;
+        }
+    } else {
+        const int nb_pad = (nb + kWave - 1) / kWave * kWave;
+        const int parts = kPlanThreads / nb_pad;     // >= 1 because nb <= kMaxBins == kPlanThreads
+        const int part = tid / nb_pad, b = tid - part * nb_pad;
+        if (part < parts && b < nb) {
             const int32_t *h = a.tile_hist + hist_off + b;
             const int me = blockIdx.x;
-#pragma unroll 16
-            for (int tl = 0; tl < a.n_tiles; ++tl) {   // independent loads, kept in flight together
+            int tot = 0, pre = 0;
+#pragma unroll 8
+            for (int tl = part; tl < a.n_tiles; tl += parts) {
                 const int v = h[(int64_t)tl * a.stride];
                 tot += v;
                 pre += tl < me ? v : 0;
             }
+            atomicAdd(&s.total[b], tot);
+            atomicAdd(&s.base[b], pre);
         }
-        s.total[b] = tot;
-        s.base[b] = pre;
-        if (blockIdx.x == 0) count_out[b] = tot;
     }
     __syncthreads();
+    if (blockIdx.x == 0)
+        for (int b = tid; b < nb; b += kPlanThreads) count_out[b] = s.total[b];
 
     // exclusive prefix sum over the keys, by wave 0: each lane owns a run of consecutive keys
     if (wave == 0) {
