@@ -113,6 +113,8 @@ def main() -> int:
     ap.add_argument("--config", default="dsv3")
     ap.add_argument("--cpu-sample-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step (plan, dispatch, combine) into one HIP graph and time its replays")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip timing the two-hop dispatch and the disaggregated multi-stage baseline")
     ap.add_argument("--probe-copy", action="store_true",
@@ -135,34 +137,66 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     cfg = W.get_config(args.config)
-    if cfg.payload != "bf16":
-        print("bench.py: only the bf16 configurations are timed here", file=sys.stderr)
-        return 2
     A, w = W.make_routing(cfg)
-    xb = W.make_activations(cfg)
-
     d_A = torch.from_numpy(A).cuda()
     d_w = torch.from_numpy(w).cuda()
-    d_x = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
     L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
-    d_expert = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
     d_out = torch.empty((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda")
+    if cfg.payload == "bf16":
+        xb = W.make_activations(cfg)
+        d_x = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+        d_expert = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+        d_y = d_expert                                   # identity experts
+        dispatch_kwargs = {}
+    else:
+        # fp8 payload + per-128-element scales travel as two planes; the experts' output is a bf16 tensor
+        # of its own (dequantisation and expert compute are outside the library)
+        q, sc = W.make_fp8_activations(cfg)
+        xb = q
+        d_x = torch.from_numpy(q).cuda()
+        d_expert = torch.empty((cfg.P, cfg.H), dtype=torch.uint8, device="cuda")
+        d_y = torch.from_numpy(W.make_expert_output(cfg).view(np.int16)).cuda().view(torch.bfloat16)
+        dispatch_kwargs = {"x_aux": torch.from_numpy(sc).cuda(),
+                           "expert_aux": torch.empty((cfg.P, sc.shape[1]), dtype=torch.float32, device="cuda")}
 
     def step():
         fusco.fusco_plan(L, d_A)
-        fusco.fusco_dispatch(L, d_x, d_expert)
-        fusco.fusco_combine(L, d_expert, d_w, d_out)
+        fusco.fusco_dispatch(L, d_x, d_expert, **dispatch_kwargs)
+        fusco.fusco_combine(L, d_y, d_w, d_out)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+
+    run_step = step
+    if args.graph:
+        # the library only enqueues kernels on the given stream (no allocation, no memset, no sync), so a
+        # step can be captured as it is; replays are checked against the eager result
+        eager_out = d_out.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):
+            d_out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(d_out, eager_out):
+                print("bench.py: graph replay differs from the eager step", file=sys.stderr)
+                return 1
+        run_step = graph.replay
 
     # timed region: exactly K steps, nothing but the library's launches between the two brackets
     K = args.steps
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(K):
-        step()
+        run_step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / K
@@ -175,16 +209,16 @@ def main() -> int:
         ev[i][0].record()
         fusco.fusco_plan(L, d_A)
         ev[i][1].record()
-        fusco.fusco_dispatch(L, d_x, d_expert)
+        fusco.fusco_dispatch(L, d_x, d_expert, **dispatch_kwargs)
         ev[i][2].record()
-        fusco.fusco_combine(L, d_expert, d_w, d_out)
+        fusco.fusco_combine(L, d_y, d_w, d_out)
         ev[i][3].record()
     torch.cuda.synchronize()
     ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
     plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
 
     variants = None
-    if not args.no_variants:
+    if not args.no_variants and cfg.payload == "bf16":
         variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
 
     if args.probe_copy:
@@ -196,13 +230,13 @@ def main() -> int:
         del src, dst
 
     # sanity: the identity-expert round trip gives sum_j w_j * x[t] = x[t] up to rounding
-    err = (d_out[:64].float() - d_x[:64].float()).abs().max().item()
+    err = (d_out[:64].float() - d_x[:64].float()).abs().max().item() if cfg.payload == "bf16" else 0.0
     if not err < 0.05:
         print("bench.py: round trip is wrong (max error %g)" % err, file=sys.stderr)
         return 1
     status = int(L.array("status").item())
 
-    bytes_dispatch = (cfg.N + cfg.P) * cfg.row_bytes            # read N rows, write P rows
+    bytes_dispatch = (cfg.N + cfg.P) * (cfg.row_bytes + cfg.aux_row_bytes)   # read N rows, write P rows
     bytes_combine = (cfg.P + cfg.N) * cfg.H * 2                 # read P rows, write N rows
     kernels = {
         "dispatch": {"ms": float(disp_ms), "algorithmic_bytes": bytes_dispatch,
@@ -226,10 +260,11 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16" if cfg.payload == "bf16" else "u8 rows + bf16 combine",
         "data": "synthetic",
-        "config": {"workload": "%s: N=%d tokens, hidden=%d bf16, E=%d, top-%d, D=%d virtual devices; step = plan + "
-                               "dispatch + combine (identity experts)" % (cfg.name, cfg.N, cfg.H, cfg.E, cfg.k, cfg.D),
+        "config": {"workload": "%s: N=%d tokens, hidden=%d %s, E=%d, top-%d, D=%d virtual devices; step = plan + "
+                               "dispatch + combine (identity experts)"
+                               % (cfg.name, cfg.N, cfg.H, cfg.payload, cfg.E, cfg.k, cfg.D),
                    "N": cfg.N, "hidden": cfg.H, "E": cfg.E, "k": cfg.k, "D": cfg.D, "seed": cfg.seed},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
@@ -239,6 +274,7 @@ def main() -> int:
         "dispatch_plus_combine": {"ms": float(disp_ms + comb_ms), "tokens_per_s": cfg.N / ((disp_ms + comb_ms) * 1e-3),
                                   "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},
         "invalid_ids": status,
+        "launch": "one HIP graph replay per step" if args.graph else "three library calls per step",
     }
     if variants is not None:
         fused = float(disp_ms + comb_ms)
