@@ -571,6 +571,109 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
     }
 }
 
+// Two-hop combine for k <= 8 in one pass: the token's k source chunks are loaded once, the partial
+// sum of every destination device is formed (same operation order as the two-kernel path: fused
+// multiply-adds in ascending j inside a device, then plain additions of the partial sums in order
+// of first appearance), stored to the device's partial row, and added to the token's output.
+struct TwoHopArgs {
+    const u32x4 *y;
+    const float *w;
+    float *partial;
+    void *out;
+    const int32_t *pair_slot, *pair_send_row;
+    const uint8_t *pair_first;
+    int32_t k;
+    int32_t C;   // 16-byte chunks per y row
+};
+
+template <bool Y_BF16, bool OUT_BF16>
+__global__ __launch_bounds__(1024) void combine_two_hop_kernel(TwoHopArgs a)
+{
+    constexpr int EPC = Y_BF16 ? 8 : 4;
+    constexpr int KMAX = 8;
+    const int t = gridDim.x - 1 - blockIdx.x;
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    const int32_t *slots = a.pair_slot + (size_t)t * a.k;
+    const int32_t *rows = a.pair_send_row + (size_t)t * a.k;
+    const uint8_t *first = a.pair_first + (size_t)t * a.k;
+    const float *wt = a.w + (size_t)t * a.k;
+
+    u32x4 v[KMAX];
+    int row[KMAX];
+    float wj[KMAX];
+    bool on[KMAX], lead[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+        on[j] = false;
+        lead[j] = false;
+        row[j] = -1;
+        if (j < a.k) {
+            const int slot = slots[j];
+            row[j] = rows[j];
+            wj[j] = wt[j];
+            lead[j] = first[j];
+            if (slot >= 0) {
+                on[j] = true;
+                v[j] = load16_stream(a.y + (size_t)slot * a.C + c);
+            }
+        }
+    }
+    float total[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) total[e] = 0.0f;
+#pragma unroll
+    for (int f = 0; f < KMAX; ++f) {
+        if (!lead[f]) continue;
+        float acc[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            if (!on[j] || row[j] != row[f]) continue;
+            if constexpr (Y_BF16) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[2 * q] = __builtin_fmaf(wj[j], bf16_lo(v[j][q]), acc[2 * q]);
+                    acc[2 * q + 1] = __builtin_fmaf(wj[j], bf16_hi(v[j][q]), acc[2 * q + 1]);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = __builtin_fmaf(wj[j], __uint_as_float(v[j][q]), acc[q]);
+            }
+        }
+        u32x4 *prow = (u32x4 *)(a.partial + ((size_t)row[f] * a.C + c) * EPC);
+#pragma unroll
+        for (int h = 0; h < EPC / 4; ++h) {
+            const u32x4 o = {__float_as_uint(acc[4 * h]), __float_as_uint(acc[4 * h + 1]),
+                             __float_as_uint(acc[4 * h + 2]), __float_as_uint(acc[4 * h + 3])};
+            prow[h] = o;
+        }
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) total[e] = total[e] + acc[e];
+    }
+    const size_t e0 = ((size_t)t * a.C + c) * EPC;
+    if constexpr (OUT_BF16) {
+        uint32_t pk[EPC / 2];
+#pragma unroll
+        for (int q = 0; q < EPC / 2; ++q) pk[q] = to_bf16(total[2 * q]) | (to_bf16(total[2 * q + 1]) << 16);
+        if constexpr (Y_BF16) {
+            const u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+            store16_through((u32x4 *)((uint16_t *)a.out + e0), o);
+        } else {
+            const u32x2 o = {pk[0], pk[1]};
+            store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < EPC / 4; ++h) {
+            const u32x4 o = {__float_as_uint(total[4 * h]), __float_as_uint(total[4 * h + 1]),
+                             __float_as_uint(total[4 * h + 2]), __float_as_uint(total[4 * h + 3])};
+            store16_through((u32x4 *)((float *)a.out + e0) + h, o);
+        }
+    }
+}
+
 // Level 1 reversed: out[t] = sum of the token's partial rows (fp32, one per destination device),
 // plain additions from +0 in the order in which the devices first appear among the token's entries.
 struct SumPartialsArgs {
@@ -794,34 +897,16 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-// Optional launch-shape override for tuning runs: "<threads>,<chunks per thread>".
-bool shape_from_env(const char *name, int *threads, int *cpt)
-{
-    const char *s = getenv(name);
-    if (!s) return false;
-    char *end = nullptr;
-    const long th = strtol(s, &end, 10);
-    if (!end || *end != ',') return false;
-    const long cp = strtol(end + 1, nullptr, 10);
-    if (th < 64 || th > 1024 || th % 64 != 0) return false;
-    if (cp != 1 && cp != 2 && cp != 4) return false;
-    *threads = (int)th;
-    *cpt = (int)cp;
-    return true;
-}
-
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? FUSCO_OK : FUSCO_ERR_HIP;
 }
 
 template <bool Y_BF16, bool OUT_BF16>
-void launch_combine(const CombineArgs &a, int N, int threads, int cpt, hipStream_t s)
+void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s)
 {
-    const int segs = (a.C + threads * cpt - 1) / (threads * cpt);
-    const dim3 grid((unsigned)N, (unsigned)segs), block((unsigned)threads);
-    if (cpt == 1) hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 1, 8>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 2, 8>), grid, block, 0, s, a);
+    const dim3 grid((unsigned)N, (unsigned)((a.C + threads - 1) / threads)), block((unsigned)threads);
+    hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 1, 8>), grid, block, 0, s, a);
 }
 
 // dst[r] = src[index(r)] for n_rows destination rows of C chunks (see gather_rows_kernel)
@@ -877,15 +962,12 @@ void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int
     a.pair_send_row = nullptr; a.send_src = nullptr; a.n_rows_dev = nullptr;
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
     // one workgroup per token whenever the row fits 1024 threads
-    int cpt = 1;
     int threads = round_up(a.C, kWave);
     if (threads > 1024) threads = 1024;
-    shape_from_env("FUSCO_COMBINE_SHAPE", &threads, &cpt);
-    if (cpt > 2) cpt = 2;
-    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, cpt, s);
-    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, cpt, s);
-    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, cpt, s);
-    else launch_combine<false, false>(a, N, threads, cpt, s);
+    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, s);
+    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, s);
+    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, s);
+    else launch_combine<false, false>(a, N, threads, s);
 }
 
 }   // namespace
@@ -1030,8 +1112,6 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     int cpt = Ct >= 512 ? 4 : (Ct >= 128 ? 2 : 1);
     int threads = round_up((Ct + cpt - 1) / cpt, kWave);
     if (threads > 256) threads = 256;
-    shape_from_env("FUSCO_DISPATCH_SHAPE", &threads, &cpt);
-    if (threads > 256) threads = 256;
     const int segs = (Ct + threads * cpt - 1) / (threads * cpt);
     const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
     hipStream_t s = (hipStream_t)stream;
@@ -1068,7 +1148,23 @@ int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, c
     const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     hipStream_t s = (hipStream_t)stream;
-    // level 2 reversed: fp32 partial row per send row
+    if (L->k <= 8) {
+        TwoHopArgs f;
+        f.y = (const u32x4 *)d_y; f.w = d_w; f.partial = d_partial; f.out = d_out;
+        f.pair_slot = L->pair_slot; f.pair_send_row = L->pair_send_row; f.pair_first = L->pair_first;
+        f.k = L->k;
+        f.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
+        int th = round_up(f.C, kWave);
+        if (th > 1024) th = 1024;
+        const dim3 fgrid((unsigned)L->N, (unsigned)((f.C + th - 1) / th));
+        if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16)
+            hipLaunchKernelGGL((combine_two_hop_kernel<true, true>), fgrid, dim3(th), 0, s, f);
+        else if (y_dtype == FUSCO_BF16) hipLaunchKernelGGL((combine_two_hop_kernel<true, false>), fgrid, dim3(th), 0, s, f);
+        else if (out_dtype == FUSCO_BF16) hipLaunchKernelGGL((combine_two_hop_kernel<false, true>), fgrid, dim3(th), 0, s, f);
+        else hipLaunchKernelGGL((combine_two_hop_kernel<false, false>), fgrid, dim3(th), 0, s, f);
+        return launch_status();
+    }
+    // general k: level 2 reversed (fp32 partial row per send row), then level 1 reversed
     CombineArgs a;
     a.y = (const u32x4 *)d_y;
     a.w = d_w;
