@@ -190,3 +190,50 @@ def test_two_hop_round_trip_returns_input_exactly(fusco):
     fusco.fusco_combine_two_hop(L, eb, torch.full((N, k), 1.0 / k, device="cuda"), part, out)
     torch.cuda.synchronize()
     assert np.array_equal(bits_host(out), xb)
+
+
+def test_calls_follow_the_given_stream_and_can_be_captured_in_a_graph(fusco, oracle):
+    """The library only enqueues on the caller's stream: a step issued on a side stream, and a step
+    captured into a HIP graph and replayed several times with eager work in between, give the eager
+    result bit for bit."""
+    rng = np.random.default_rng(21)
+    N, k, E, D, H = 700, 8, 64, 8, 1024
+    A = random_topk(rng, N, k, E)
+    xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
+    w = rng.random((N, k)).astype(np.float32)
+    want = oracle.plan(A, E, D)
+    _, expert_want = oracle.dispatch(want, xb)
+    _, out_want = oracle.combine_f32(expert_want, w, want.pair_slot)
+    d_A, d_x, d_w = dev(A), bf16_dev(xb), dev(w)
+    L = fusco.Layout(N, k, E, D)
+    eb = torch.zeros((N * k, H), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((N, H), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        fusco.fusco_plan(L, d_A)
+        fusco.fusco_dispatch(L, d_x, eb)
+        fusco.fusco_combine(L, eb, d_w, out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    side.synchronize()
+    assert np.array_equal(bits_host(eb), expert_want) and np.array_equal(bits_host(out), out_want)
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i in range(4):
+        eb.zero_()
+        out.zero_()
+        L.mem.fill_(0x5A)                  # eager work between the replays; the plan must be rebuilt by the graph
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_host(eb), expert_want), i
+        assert np.array_equal(bits_host(out), out_want), i
+        got = L.to_host()
+        assert np.array_equal(got.pair_slot, want.pair_slot) and np.array_equal(got.send_src, want.send_src)
