@@ -105,6 +105,50 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
             "disaggregated_combine_ms": dis_c, "reps": reps}
 
 
+def measure_ceilings(fusco, torch, cfg, d_x, d_expert, d_out, reps):
+    """What the memory system gives for plain row traffic of the same sizes, measured with the library's probe
+    kernels (no plan, no arithmetic): the figures the shuffle kernels' bandwidth is to be read against."""
+    row = cfg.row_bytes
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    xb = d_x.view(torch.uint8).view(cfg.N, -1)
+    eb = d_expert.view(torch.uint8).view(cfg.P, -1)
+    ob = d_out.view(torch.uint8).view(cfg.N, -1)
+    eb2 = torch.empty_like(eb)
+
+    def gbps(nbytes, fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return nbytes / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+
+    P, N = cfg.P, cfg.N
+    out = {"row_bytes": row, "reps": reps, "unit": "GB/s"}
+    for name, scatter in (("launch_order", False), ("scattered_rows", True)):
+        out[name] = {
+            "fill_P_rows": gbps(P * row, lambda: fusco.fusco_probe_rows(None, eb, 0, 1, scatter)),
+            "read_P_rows": gbps(P * row, lambda: fusco.fusco_probe_rows(eb, None, 1, 0, scatter, sink=sink)),
+            "copy_P_rows": gbps(2 * P * row, lambda: fusco.fusco_probe_rows(eb, eb2, 1, 1, scatter)),
+            "read_1_write_8": gbps((N + P) * row, lambda: fusco.fusco_probe_rows(xb, eb, 1, 8, scatter)),
+            "read_8_write_1": gbps((N + P) * row, lambda: fusco.fusco_probe_rows(eb, ob, 8, 1, scatter, True)),
+        }
+    # the same bytes as one stream of 4 KiB pieces, one 16-byte store (or load) per thread, in address order:
+    # the best the memory system gives for writes (a single front) and for a copy
+    if (P * row) % 4096 == 0:
+        f1, f2 = eb.view(-1, 4096), eb2.view(-1, 4096)
+        out["one_front_4KiB_pieces"] = {
+            "fill": gbps(P * row, lambda: fusco.fusco_probe_rows(None, f1, 0, 1, False)),
+            "read": gbps(P * row, lambda: fusco.fusco_probe_rows(f1, None, 1, 0, False, sink=sink)),
+            "copy": gbps(2 * P * row, lambda: fusco.fusco_probe_rows(f1, f2, 1, 1, False)),
+        }
+    del eb2
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,8 +159,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step (plan, dispatch, combine) into one HIP graph and time its replays")
+    ap.add_argument("--cold-sets", type=int, default=1,
+                    help="rotate the step over this many copies of its buffers (cache-cold figures for the small "
+                         "configurations; choose enough copies to exceed 512 MB)")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip timing the two-hop dispatch and the disaggregated multi-stage baseline")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the plain row-traffic probes (fill, read, copy, 1:8 and 8:1 mixes) of the same sizes")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -159,16 +208,30 @@ def main() -> int:
         dispatch_kwargs = {"x_aux": torch.from_numpy(sc).cuda(),
                            "expert_aux": torch.empty((cfg.P, sc.shape[1]), dtype=torch.float32, device="cuda")}
 
+    # cold runs: the step walks over R copies of its buffers (same contents), so that a configuration
+    # small enough to live in the 256 MB memory-side cache finds none of its rows there
+    sets = [(d_x, d_expert, d_y, d_out, dispatch_kwargs)]
+    for _ in range(1, max(1, args.cold_sets)):
+        kw = {name: t.clone() for name, t in dispatch_kwargs.items()}
+        e = torch.empty_like(d_expert)
+        sets.append((d_x.clone(), e, e if d_y is d_expert else d_y.clone(), torch.empty_like(d_out), kw))
+    turn = [0]
+
     def step():
+        sx, se, sy, so, kw = sets[turn[0] % len(sets)]
+        turn[0] += 1
         fusco.fusco_plan(L, d_A)
-        fusco.fusco_dispatch(L, d_x, d_expert, **dispatch_kwargs)
-        fusco.fusco_combine(L, d_y, d_w, d_out)
+        fusco.fusco_dispatch(L, sx, se, **kw)
+        fusco.fusco_combine(L, sy, d_w, so)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
     run_step = step
+    if args.graph and len(sets) > 1:
+        print("bench.py: --graph replays one captured step and cannot rotate buffers", file=sys.stderr)
+        return 2
     if args.graph:
         # the library only enqueues kernels on the given stream (no allocation, no memset, no sync), so a
         # step can be captured as it is; replays are checked against the eager result
@@ -206,12 +269,13 @@ def main() -> int:
     # call (an event costs about 5 us of stream time, which is why they stay out of the region above)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
     for i in range(K):
+        sx, se, sy, so, kw = sets[i % len(sets)]
         ev[i][0].record()
         fusco.fusco_plan(L, d_A)
         ev[i][1].record()
-        fusco.fusco_dispatch(L, d_x, d_expert, **dispatch_kwargs)
+        fusco.fusco_dispatch(L, sx, se, **kw)
         ev[i][2].record()
-        fusco.fusco_combine(L, d_y, d_w, d_out)
+        fusco.fusco_combine(L, sy, d_w, so)
         ev[i][3].record()
     torch.cuda.synchronize()
     ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
@@ -220,6 +284,14 @@ def main() -> int:
     variants = None
     if not args.no_variants and cfg.payload == "bf16":
         variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
+
+    ceilings = None
+    if not args.no_ceilings and cfg.payload == "bf16":
+        ceilings = measure_ceilings(fusco, torch, cfg, d_x, d_expert, d_out, max(10, K // 10))
+        # the probes overwrote the shuffle's buffers: run one more step so the checks below see its results
+        turn[0] = 0
+        step()
+        torch.cuda.synchronize()
 
     if args.probe_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
@@ -238,12 +310,16 @@ def main() -> int:
 
     bytes_dispatch = (cfg.N + cfg.P) * (cfg.row_bytes + cfg.aux_row_bytes)   # read N rows, write P rows
     bytes_combine = (cfg.P + cfg.N) * cfg.H * 2                 # read P rows, write N rows
+    def spread(col):
+        p10, med, p90 = np.percentile(ms[:, col], [10, 50, 90])
+        return {"p10_ms": float(p10), "median_ms": float(med), "p90_ms": float(p90)}
+
     kernels = {
-        "dispatch": {"ms": float(disp_ms), "algorithmic_bytes": bytes_dispatch,
+        "dispatch": {"ms": float(disp_ms), **spread(1), "algorithmic_bytes": bytes_dispatch,
                      "GBps": bytes_dispatch / (disp_ms * 1e-3) / 1e9},
-        "combine": {"ms": float(comb_ms), "algorithmic_bytes": bytes_combine,
+        "combine": {"ms": float(comb_ms), **spread(2), "algorithmic_bytes": bytes_combine,
                     "GBps": bytes_combine / (comb_ms * 1e-3) / 1e9},
-        "plan": {"ms": float(plan_ms)},
+        "plan": {"ms": float(plan_ms), **spread(0)},
     }
     dom = "dispatch" if disp_ms >= comb_ms else "combine"
     achieved = kernels[dom]["GBps"]
@@ -275,7 +351,10 @@ def main() -> int:
                                   "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},
         "invalid_ids": status,
         "launch": "one HIP graph replay per step" if args.graph else "three library calls per step",
+        "buffer_sets": len(sets),
     }
+    if ceilings is not None:
+        result["ceilings"] = ceilings
     if variants is not None:
         fused = float(disp_ms + comb_ms)
         variants["fused_dispatch_plus_combine_ms"] = fused

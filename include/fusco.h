@@ -244,6 +244,23 @@ int fusco_segments_copy(const void *d_src, uint64_t src_bytes, const fusco_segme
  */
 int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream);
 
+/*
+ * Measurement aid: whole-row traffic of a chosen shape, with no plan behind it and no arithmetic.
+ * One workgroup reads `reads_per_group` rows of d_src (XOR-ing them) and writes `writes_per_group`
+ * rows of d_dst; supported shapes (reads, writes): (0,1) fill, (1,0) read, (1,1) copy, (1,8) the
+ * dispatch mix, (8,1) the combine mix.  The grid is dst_rows / writes_per_group workgroups (for
+ * (1,0): src_rows); dst_rows must be a multiple of writes_per_group and src_rows must hold
+ * groups * reads_per_group rows.  scatter == 0 walks both buffers in launch order; otherwise row i of
+ * a stream sits at (i * m) mod rows with m coprime to the row count, i.e. rows land far from their
+ * launch-order neighbours as they do under routing.  write_through != 0 uses the write-through stores
+ * of the combine kernel, else plain stores.  d_sink (one uint32 in device memory) is needed for
+ * (1,0) only and is never written in practice.  Buffers: [src_rows, row_bytes], [dst_rows,
+ * row_bytes], 16-byte aligned, row_bytes a multiple of 16.  Returns FUSCO_ERR_INVALID_ARG otherwise.
+ */
+int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t dst_rows, size_t row_bytes,
+                     int reads_per_group, int writes_per_group, int scatter, int write_through,
+                     uint32_t *d_sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy",
+           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy", "fusco_probe_rows",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -77,6 +77,9 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.fusco_probe_rows.restype = ctypes.c_int
+    lib.fusco_probe_rows.argtypes = [vp, u32, vp, u32, sz, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                     vp, vp]
     lp = ctypes.POINTER(_CLayout)
     u64, i64 = ctypes.c_uint64, ctypes.c_int64
     lib.fusco_segments_scan.restype = ctypes.c_int
@@ -316,6 +319,27 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise FuscoError("dst is smaller than src")
     _check(load_library().fusco_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
            "fusco_probe_copy")
+
+
+def fusco_probe_rows(src, dst, reads: int, writes: int, scatter: bool, write_through: bool = False,
+                     sink: torch.Tensor | None = None, stream=None) -> None:
+    """src / dst: 2-D contiguous device tensors of rows with the same row size in bytes (either may be None
+    when its side is unused); sink: one int32 on the device, needed for the read-only shape."""
+    rows, row_bytes = [0, 0], 0
+    for i, t in enumerate((src, dst)):
+        if t is None:
+            continue
+        if not t.is_cuda or t.dim() != 2 or not t.is_contiguous():
+            raise FuscoError("probe rows needs 2-D contiguous device tensors")
+        rb = t.shape[1] * t.element_size()
+        if row_bytes and rb != row_bytes:
+            raise FuscoError("src and dst rows differ in size")
+        rows[i], row_bytes = t.shape[0], rb
+    if sink is not None and (not sink.is_cuda or sink.numel() < 1 or sink.element_size() != 4):
+        raise FuscoError("sink must be one 32-bit word on the device")
+    _check(load_library().fusco_probe_rows(_ptr(src), rows[0], _ptr(dst), rows[1], row_bytes, int(reads), int(writes),
+                                           int(bool(scatter)), int(bool(write_through)), _ptr(sink), _stream(stream)),
+           "fusco_probe_rows")
 
 
 def fusco_disaggregated_plan(rank_layout: Layout, layout: Layout, topk_idx: torch.Tensor, topk_dev: torch.Tensor,

@@ -893,7 +893,64 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(u32x4 *dst, const u32x4
     if (i < n) dst[i] = load16_stream(src + i);
 }
 
+// Measurement aid: row traffic of a chosen shape with no planning and no arithmetic.  Workgroup b reads
+// R rows of `src` and writes W rows of `dst`; row i of a stream sits at (i * mul) mod rows, so mul == 1
+// walks the buffer in launch order and a multiplier coprime to the row count scatters the rows the way
+// a routed shuffle does.  The rows read are XOR-ed so that every load is live.
+struct ProbeRowsArgs {
+    const u32x4 *src;
+    u32x4 *dst;
+    uint32_t *sink;
+    uint32_t src_rows, dst_rows;
+    uint32_t src_mul, dst_mul;
+    uint32_t C;          // 16-byte units per row
+    uint32_t through;    // 1: write-through stores
+};
+
+template <int R, int W>
+__global__ __launch_bounds__(256) void probe_rows_kernel(ProbeRowsArgs a)
+{
+    const uint32_t b = blockIdx.x;
+    size_t src_row[R > 0 ? R : 1], dst_row[W > 0 ? W : 1];
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+        src_row[i] = (size_t)(((uint64_t)b * R + i) * a.src_mul % a.src_rows) * a.C;
+#pragma unroll
+    for (int i = 0; i < W; ++i)
+        dst_row[i] = (size_t)(((uint64_t)b * W + i) * a.dst_mul % a.dst_rows) * a.C;
+    u32x4 seen = {0u, 0u, 0u, 0u};
+    for (uint32_t c = threadIdx.x; c < a.C; c += 256) {
+        u32x4 v[R > 0 ? R : 1];
+        u32x4 acc = {R == 0 ? b : 0u, R == 0 ? c : 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < R; ++i) v[i] = load16_stream(a.src + src_row[i] + c);
+#pragma unroll
+        for (int i = 0; i < R; ++i) acc ^= v[i];
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            if (a.through) store16_through(a.dst + dst_row[i] + c, acc);
+            else a.dst[dst_row[i] + c] = acc;
+        }
+        seen ^= acc;
+    }
+    if (W == 0 && (seen.x ^ seen.y ^ seen.z ^ seen.w) == 0x9E3779B9u && a.sink) a.sink[0] = b;
+}
+
+
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// odd multiplier close to frac * n that shares no factor with n: i -> i * mul mod n is a bijection of
+// [0, n) that sends neighbours far apart
+uint32_t coprime_near(uint32_t n, double frac)
+{
+    if (n < 3) return 1u;
+    uint32_t m = (uint32_t)((double)n * frac) | 1u;
+    for (;; m += 2) {
+        uint32_t x = n, y = m % n;
+        while (y) { const uint32_t r = x % y; x = y; y = r; }
+        if (x == 1 && m % n != 0) return m % n;
+    }
+}
 
 int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
@@ -1318,6 +1375,38 @@ int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream)
     if (blocks > 0x7FFFFFFFu) return FUSCO_ERR_INVALID_ARG;
     hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        (u32x4 *)d_dst, (const u32x4 *)d_src, n);
+    return launch_status();
+}
+
+int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t dst_rows, size_t row_bytes,
+                     int reads_per_group, int writes_per_group, int scatter, int write_through,
+                     uint32_t *d_sink, void *stream)
+{
+    const int R = reads_per_group, W = writes_per_group;
+    const bool shape_ok = (R == 0 && W == 1) || (R == 1 && W == 0) || (R == 1 && W == 1) || (R == 1 && W == 8) ||
+                          (R == 8 && W == 1);
+    if (!shape_ok || row_bytes == 0 || row_bytes % 16 != 0 || row_bytes / 16 > 0xFFFFFFFFu) return FUSCO_ERR_INVALID_ARG;
+    if ((R > 0 && (!d_src || !aligned16(d_src) || src_rows == 0)) || (W > 0 && (!d_dst || !aligned16(d_dst) || dst_rows == 0)))
+        return FUSCO_ERR_INVALID_ARG;
+    if (W == 0 && !d_sink) return FUSCO_ERR_INVALID_ARG;
+    // every workgroup moves whole rows: the stream that fixes the grid must divide evenly
+    const uint32_t groups = W > 0 ? dst_rows / (uint32_t)W : src_rows / (uint32_t)R;
+    if (W > 0 && dst_rows % (uint32_t)W != 0) return FUSCO_ERR_INVALID_ARG;
+    if (R > 0 && (uint64_t)groups * (uint64_t)R > src_rows) return FUSCO_ERR_INVALID_ARG;
+    if (groups == 0) return FUSCO_OK;
+    ProbeRowsArgs a;
+    a.src = (const u32x4 *)d_src; a.dst = (u32x4 *)d_dst; a.sink = d_sink;
+    a.src_rows = src_rows ? src_rows : 1; a.dst_rows = dst_rows ? dst_rows : 1;
+    a.src_mul = scatter ? coprime_near(a.src_rows, 0.3819660112501051) : 1u;
+    a.dst_mul = scatter ? coprime_near(a.dst_rows, 0.6180339887498949) : 1u;
+    a.C = (uint32_t)(row_bytes / 16); a.through = write_through ? 1u : 0u;
+    const dim3 grid(groups), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    if (R == 0) hipLaunchKernelGGL((probe_rows_kernel<0, 1>), grid, block, 0, s, a);
+    else if (W == 0) hipLaunchKernelGGL((probe_rows_kernel<1, 0>), grid, block, 0, s, a);
+    else if (R == 1 && W == 1) hipLaunchKernelGGL((probe_rows_kernel<1, 1>), grid, block, 0, s, a);
+    else if (R == 1) hipLaunchKernelGGL((probe_rows_kernel<1, 8>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((probe_rows_kernel<8, 1>), grid, block, 0, s, a);
     return launch_status();
 }
 

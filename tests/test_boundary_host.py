@@ -160,6 +160,16 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_copy(buf, buf + 4, 64, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4096, 24, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4096, 0, None) == 0
+    # probe rows: unsupported shapes, bad sizes, missing buffers (nothing is launched on error)
+    pr = lib.fusco_probe_rows
+    assert pr(buf, 8, buf + 4096, 8, 64, 2, 1, 0, 0, None, None) == -1        # shape not offered
+    assert pr(buf, 8, buf + 4096, 8, 24, 1, 1, 0, 0, None, None) == -1        # row size not a multiple of 16
+    assert pr(None, 8, buf + 4096, 8, 64, 1, 1, 0, 0, None, None) == -1
+    assert pr(buf, 8, None, 8, 64, 1, 1, 0, 0, None, None) == -1
+    assert pr(buf, 8, buf + 4096, 12, 64, 1, 8, 0, 0, None, None) == -1       # 12 rows do not split into groups of 8
+    assert pr(buf, 1, buf + 4096, 16, 64, 1, 8, 0, 0, None, None) == -1       # 2 groups need 2 source rows
+    assert pr(buf, 8, None, 0, 64, 1, 0, 0, 0, None, None) == -1              # read-only shape needs the sink
+    assert pr(buf, 8, buf + 4100, 8, 64, 1, 1, 0, 0, None, None) == -1        # misaligned
 
 
 def test_product_package_does_not_touch_the_oracle():
