@@ -41,12 +41,30 @@ bool sizes_ok(int32_t N, int32_t k, int32_t E, int32_t D)
     return true;
 }
 
+// From this many tiles on, per-tile counts are first summed over chunks of tiles (one more small launch),
+// so that a placement workgroup reads about 2 * sqrt(tiles) rows of counts instead of one per tile.
+constexpr int kChunkMinTiles = 96;
+
 inline int tokens_per_tile(int k) { return kTilePairs / k; }
 inline int num_tiles(int N, int k)
 {
     const int tpt = tokens_per_tile(k);
     const int n = (N + tpt - 1) / tpt;
     return n < 1 ? 1 : n;
+}
+
+// tiles per chunk (a power of two near sqrt(n_tiles)), or 0 when the tiles are few enough to be read one by one
+inline int chunk_tiles_for(int n_tiles)
+{
+    if (n_tiles < kChunkMinTiles) return 0;
+    int c = 8;
+    while (c * c < n_tiles) c *= 2;
+    return c;
+}
+inline int num_chunks(int n_tiles)
+{
+    const int c = chunk_tiles_for(n_tiles);
+    return c ? (n_tiles + c - 1) / c : 0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -60,6 +78,8 @@ struct PlanArgs {
     int32_t n_tiles;
     int32_t stride;   // ints per tile in tile_hist: E expert counts, D device counts, 1 invalid count
     int32_t *tile_hist;
+    int32_t chunk_tiles, n_chunks;   // 0, 0: no chunk level
+    int32_t *chunk_hist;             // [n_chunks][stride]: tile_hist summed over the tiles of a chunk
     int32_t *exp_count, *exp_off, *send_count, *send_off;
     int32_t *pair_slot, *slot_pair, *slot_token, *send_src, *pair_send_row, *slot_send_row;
     uint8_t *pair_first;
@@ -170,6 +190,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
     for (int b = tid; b <= nb; b += kPlanThreads) out[b] = hist[b];
 }
 
+// Optional pass between counting and placing: sums the per-tile counts over chunks of consecutive
+// tiles.  One workgroup per chunk; the columns are covered 1024 at a time, and where fewer columns
+// than threads remain the tiles of the chunk are split over groups of threads.
+__global__ __launch_bounds__(kPlanThreads) void plan_chunk_kernel(PlanArgs a)
+{
+    __shared__ int acc[kPlanThreads];
+    const int tid = threadIdx.x;
+    const int chunk = blockIdx.x;
+    const int t0 = chunk * a.chunk_tiles, t1 = min(t0 + a.chunk_tiles, a.n_tiles);
+    for (int col0 = 0; col0 < a.stride; col0 += kPlanThreads) {
+        const int ncol = min(a.stride - col0, kPlanThreads);
+        const int pad = (ncol + kWave - 1) / kWave * kWave;
+        const int parts = kPlanThreads / pad;
+        const int part = tid / pad, b = tid - part * pad;
+        acc[tid] = 0;
+        __syncthreads();
+        if (part < parts && b < ncol) {
+            const int32_t *h = a.tile_hist + col0 + b;
+            int sum = 0;
+#pragma unroll 8
+            for (int tl = t0 + part; tl < t1; tl += parts) sum += h[(int64_t)tl * a.stride];
+            atomicAdd(&acc[b], sum);
+        }
+        __syncthreads();
+        if (tid < ncol) a.chunk_hist[(int64_t)chunk * a.stride + col0 + tid] = acc[tid];
+        __syncthreads();
+    }
+}
+
 // Shared LDS state of the placement kernel.
 struct PlaceLds {
     int16_t tile_dev[kTilePairs];              // device of every pair, -1 for an invalid expert id
@@ -232,11 +281,25 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
             const int32_t *h = a.tile_hist + hist_off + b;
             const int me = blockIdx.x;
             int tot = 0, pre = 0;
+            if (a.chunk_tiles == 0) {
 #pragma unroll 8
-            for (int tl = part; tl < a.n_tiles; tl += parts) {
-                const int v = h[(int64_t)tl * a.stride];
-                tot += v;
-                pre += tl < me ? v : 0;
+                for (int tl = part; tl < a.n_tiles; tl += parts) {
+                    const int v = h[(int64_t)tl * a.stride];
+                    tot += v;
+                    pre += tl < me ? v : 0;
+                }
+            } else {
+                // whole chunks from their sums, then the tiles of this workgroup's own chunk before it
+                const int32_t *ch = a.chunk_hist + hist_off + b;
+                const int my_chunk = me / a.chunk_tiles;
+#pragma unroll 8
+                for (int c = part; c < a.n_chunks; c += parts) {
+                    const int v = ch[(int64_t)c * a.stride];
+                    tot += v;
+                    pre += c < my_chunk ? v : 0;
+                }
+#pragma unroll 8
+                for (int tl = my_chunk * a.chunk_tiles + part; tl < me; tl += parts) pre += h[(int64_t)tl * a.stride];
             }
             atomicAdd(&s.total[b], tot);
             atomicAdd(&s.base[b], pre);
@@ -368,12 +431,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         a.pair_send_row[pair0 + p] = srow;
     }
 
-    if (blockIdx.x == 0 && tid == 0) {
+    if (blockIdx.x == 0 && wave == 0) {
         int bad = 0;
-        if constexpr (SINGLE) bad = s.invalid;
-        else
-            for (int tl = 0; tl < a.n_tiles; ++tl) bad += a.tile_hist[(int64_t)tl * a.stride + a.E + a.D];
-        *a.status = bad;
+        if constexpr (SINGLE) {
+            bad = s.invalid;
+        } else {
+            // the last column of the counts holds the invalid ids of a tile (or of a chunk of tiles)
+            const int32_t *col = (a.chunk_tiles ? a.chunk_hist : a.tile_hist) + a.E + a.D;
+            const int rows = a.chunk_tiles ? a.n_chunks : a.n_tiles;
+            for (int r = lane; r < rows; r += kWave) bad += col[(int64_t)r * a.stride];
+            for (int d = kWave / 2; d > 0; d >>= 1) bad += __shfl_down(bad, d, kWave);
+        }
+        if (lane == 0) *a.status = bad;
     }
 }
 
@@ -1087,7 +1156,8 @@ size_t fusco_layout_bytes(int32_t N, int32_t k, int32_t E, int32_t D)
 size_t fusco_scratch_bytes(int32_t N, int32_t k, int32_t E, int32_t D)
 {
     if (!sizes_ok(N, k, E, D)) return 0;
-    return align_up((size_t)num_tiles(N, k) * (size_t)(E + D + 1) * 4, 256);
+    const int tiles = num_tiles(N, k);
+    return align_up(((size_t)tiles + (size_t)num_chunks(tiles)) * (size_t)(E + D + 1) * 4, 256);
 }
 
 int fusco_layout_bind(fusco_layout *L, int32_t N, int32_t k, int32_t E, int32_t D, void *d_mem, size_t bytes)
@@ -1120,6 +1190,9 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
     a.n_tiles = num_tiles(L->N, L->k);
     a.stride = L->E + L->D + 1;
     a.tile_hist = (int32_t *)d_scratch;
+    a.chunk_tiles = chunk_tiles_for(a.n_tiles);
+    a.n_chunks = num_chunks(a.n_tiles);
+    a.chunk_hist = a.tile_hist + (size_t)a.n_tiles * (size_t)a.stride;
     a.exp_count = L->exp_count; a.exp_off = L->exp_off; a.send_count = L->send_count; a.send_off = L->send_off;
     a.pair_slot = L->pair_slot; a.slot_pair = L->slot_pair; a.slot_token = L->slot_token; a.send_src = L->send_src;
     a.pair_send_row = L->pair_send_row; a.slot_send_row = L->slot_send_row; a.pair_first = L->pair_first;
@@ -1129,6 +1202,7 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
         hipLaunchKernelGGL(plan_place_kernel<true>, dim3(1), dim3(kPlanThreads), 0, s, a);
     } else {
         hipLaunchKernelGGL(plan_count_kernel, dim3(a.n_tiles), dim3(kPlanThreads), 0, s, a);
+        if (a.n_chunks > 0) hipLaunchKernelGGL(plan_chunk_kernel, dim3(a.n_chunks), dim3(kPlanThreads), 0, s, a);
         hipLaunchKernelGGL(plan_place_kernel<false>, dim3(a.n_tiles), dim3(kPlanThreads), 0, s, a);
     }
     return launch_status();

@@ -65,6 +65,12 @@ PLAN_SHAPES = [
     (900, 4, 64, 1, True),         # single device
     (1300, 5, 10, 5, False),       # repeated experts inside a token
     (2100, 7, 7, 7, False), (129, 33, 66, 2, True),
+    # many tiles: per-tile counts are summed over chunks of tiles first (from 96 tiles on)
+    (24320, 8, 256, 8, False),     # 95 tiles: the last size read tile by tile
+    (24321, 8, 256, 8, False),     # 96 tiles, the last one holding one token
+    (30011, 8, 64, 16, True),      # 118 tiles, ragged
+    (3200, 64, 1024, 1024, True),  # 100 tiles, more count columns than threads
+    (600000, 8, 32, 4, False),     # 2344 tiles, chunks of 64, last chunk ragged
 ]
 
 
@@ -112,9 +118,10 @@ def test_plan_is_deterministic(fusco):
         assert torch.equal(L.mem, ref)
 
 
-def test_plan_counts_invalid_ids(fusco, oracle):
+@pytest.mark.parametrize("N", [700, 60000])          # one-level and chunked counts
+def test_plan_counts_invalid_ids(fusco, oracle, N):
     rng = np.random.default_rng(77)
-    N, k, E, D = 700, 4, 32, 4
+    k, E, D = 4, 32, 4
     A = random_topk(rng, N, k, E)
     bad = rng.choice(N * k, size=9, replace=False)
     Ab = A.copy().reshape(-1)
