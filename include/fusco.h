@@ -39,6 +39,7 @@ extern "C" {
 
 #define FUSCO_MAX_K 64   /* experts per token                    */
 #define FUSCO_MAX_E 1024 /* experts (and therefore devices)      */
+#define FUSCO_MAX_ROW_BYTES (1u << 20) /* one row of the movers, both planes of a dispatch together */
 
 /* element types of fusco_combine */
 #define FUSCO_BF16 0
@@ -119,7 +120,8 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
  *     send_buf[pair_send_row[t*k+j]] = x[t] where pair_first       (FUSCO_DISPATCH_WIRE)
  * Rows are opaque bytes.  d_x: [N, row_bytes], row_bytes a positive multiple of 16.  An optional
  * second plane (e.g. per-block scales of an fp8 payload) of aux_row_bytes (multiple of 16, or 0
- * with NULL aux pointers) follows the same descriptors.  d_expert_buf: [P, row_bytes],
+ * with NULL aux pointers) follows the same descriptors; row_bytes + aux_row_bytes may not exceed
+ * FUSCO_MAX_ROW_BYTES.  d_expert_buf: [P, row_bytes],
  * d_expert_aux: [P, aux_row_bytes]; d_send_buf: [send_cap, row_bytes], d_send_aux likewise; rows
  * >= U of the send buffers are not written.  Buffers of a plane that is not requested by `flags`
  * may be NULL.
@@ -139,7 +141,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
  * accumulated in fp32 with one fused multiply-add per term in ascending j from +0, then rounded
  * once (nearest even) when out_dtype is FUSCO_BF16.
  * d_y: [P, H] of y_dtype, d_w: [N, k] fp32, d_out: [N, H] of out_dtype.  H * sizeof(y element)
- * must be a multiple of 16.  `flags` must be 0.
+ * must be a multiple of 16 and at most FUSCO_MAX_ROW_BYTES.  `flags` must be 0.
  */
 int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, void *d_out,
                   int out_dtype, int32_t H, uint32_t flags, void *stream);

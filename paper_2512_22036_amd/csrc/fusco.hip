@@ -26,7 +26,7 @@ constexpr int kTilePairs = 2048;                        // (token, expert) pairs
 constexpr int kRounds = kTilePairs / kPlanThreads;      // 64-pair rounds per wave
 constexpr int kWaveChunk = kTilePairs / kPlanWaves;     // consecutive pairs owned by one wave
 constexpr int kMaxBins = FUSCO_MAX_E;
-constexpr size_t kMaxRowChunks = 1u << 16;              // rows of at most 1 MiB
+constexpr size_t kMaxRowChunks = FUSCO_MAX_ROW_BYTES / 16;
 
 static_assert(kTilePairs >= FUSCO_MAX_K, "a tile must hold at least one token");
 static_assert(kMaxBins <= kPlanThreads, "the planner gives every bin a thread");

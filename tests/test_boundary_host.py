@@ -103,6 +103,8 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert d(buf, 64, None, 0, buf, None, None, None, 8, None) == -3             # unknown flag
     assert d(buf, 64, None, 0, buf, None, None, None, 4, None) == -1             # two-hop needs the send buffer
     assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
+    assert d(buf, (1 << 20) + 16, None, 0, buf, None, None, None, 0, None) == -1 # just above FUSCO_MAX_ROW_BYTES
+    assert d(buf, 1 << 20, buf, 16, buf, buf, None, None, 0, None) == -1         # the two planes together are
     # combine
     c = lambda *a: lib.fusco_combine(ctypes.byref(L), *a)
     assert c(None, 0, buf, buf, 0, 64, 0, None) == -1
@@ -115,6 +117,8 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert c(buf, 0, buf, buf, 7, 64, 0, None) == -3
     assert c(buf, 0, buf, buf, 0, 64, 1, None) == -3          # flags must be 0
     assert c(buf + 8, 0, buf, buf, 0, 64, 0, None) == -1
+    assert c(buf, 0, buf, buf, 0, (1 << 19) + 8, 0, None) == -1   # bf16 row above FUSCO_MAX_ROW_BYTES
+    assert c(buf, 1, buf, buf, 0, (1 << 18) + 4, 0, None) == -1   # fp32 row above it
     # two-hop combine
     th = lambda *a: lib.fusco_combine_two_hop(ctypes.byref(L), *a)
     assert th(buf, 0, buf, None, buf, 0, 64, None) == -1          # no partial tensor

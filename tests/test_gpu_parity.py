@@ -155,6 +155,8 @@ DISPATCH_SHAPES = [
     # N, k, E, D, row_bytes
     (33, 2, 8, 4, 16), (100, 4, 16, 4, 48), (257, 8, 64, 8, 2048), (300, 8, 256, 8, 14336),
     (513, 2, 16, 4, 16 * 37), (64, 3, 6, 3, 16 * 129), (40, 8, 32, 32, 16 * 1025), (1, 1, 1, 1, 4096),
+    (5, 2, 4, 2, 1 << 20),         # the largest row the movers take (1 MiB)
+    (7, 3, 6, 3, (1 << 20) - 16),
 ]
 
 
@@ -231,6 +233,8 @@ COMBINE_SHAPES = [
     # N, k, E, D, H
     (50, 2, 8, 4, 8), (129, 8, 64, 8, 1024), (300, 8, 256, 8, 7168), (65, 4, 16, 4, 8 * 37),
     (40, 1, 4, 2, 512), (33, 9, 18, 6, 8 * 129), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096),
+    (3, 2, 4, 2, 1 << 19),         # the largest row (1 MiB of bf16)
+    (4, 3, 6, 2, 8 * 8191 + 8),
 ]
 
 
