@@ -14,6 +14,8 @@
  *     argument of fusco_combine may be the expert buffer fusco_dispatch wrote.
  *   - Return value: FUSCO_OK (0) when the work was enqueued, a negative FUSCO_ERR_* otherwise.
  *     On an error nothing is launched.
+ *   - A layout with N == 0 is valid everywhere: sizes are still checked, tensor pointers (all of
+ *     them empty then) may be NULL, nothing is launched by the movers and FUSCO_OK is returned.
  *   - Expert-parallel devices are D virtual partitions of one GPU's buffers.  Expert e lives on
  *     device e / (E / D) (contiguous placement; E must be a multiple of D).
  *   - All row orders are deterministic: rows of one expert, and rows of one device's receive

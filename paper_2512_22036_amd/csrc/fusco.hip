@@ -1064,9 +1064,11 @@ void launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
                        (const u32x4 *)src, n);
 }
 
-int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_out, int out_dtype, int32_t H)
+// `empty`: the layout has no tokens, so the tensors hold no rows and may be NULL
+int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_out, int out_dtype, int32_t H,
+                  bool empty)
 {
-    if (!d_y || !d_w || !d_out || H <= 0) return FUSCO_ERR_INVALID_ARG;
+    if (H <= 0 || (!empty && (!d_y || !d_w || !d_out))) return FUSCO_ERR_INVALID_ARG;
     if ((y_dtype != FUSCO_BF16 && y_dtype != FUSCO_F32) || (out_dtype != FUSCO_BF16 && out_dtype != FUSCO_F32))
         return FUSCO_ERR_UNSUPPORTED;
     const size_t y_row = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
@@ -1212,7 +1214,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
                    void *d_send_aux, uint32_t flags, void *stream)
 {
-    if (!layout_ok(L) || !d_x) return FUSCO_ERR_INVALID_ARG;
+    if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
     if (flags == 0) flags = FUSCO_DISPATCH_EXPERT;
     if (flags & ~(FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE | FUSCO_DISPATCH_TWO_HOP)) return FUSCO_ERR_UNSUPPORTED;
     const bool two_hop = flags & FUSCO_DISPATCH_TWO_HOP;
@@ -1220,13 +1222,13 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     const bool expert = flags & FUSCO_DISPATCH_EXPERT, wire = flags & FUSCO_DISPATCH_WIRE;
     if (row_bytes == 0 || row_bytes % 16 != 0 || aux_row_bytes % 16 != 0) return FUSCO_ERR_INVALID_ARG;
     if ((row_bytes + aux_row_bytes) / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
-    if (aux_row_bytes && !d_x_aux) return FUSCO_ERR_INVALID_ARG;
+    if (L->N == 0) return FUSCO_OK;   // nothing to move: the (empty) tensors may be NULL
+    if (!d_x || (aux_row_bytes && !d_x_aux)) return FUSCO_ERR_INVALID_ARG;
     if (expert && (!d_expert_buf || (aux_row_bytes && !d_expert_aux))) return FUSCO_ERR_INVALID_ARG;
     if (wire && (!d_send_buf || (aux_row_bytes && !d_send_aux))) return FUSCO_ERR_INVALID_ARG;
     if (!aligned16(d_x) || !aligned16(d_x_aux) || !aligned16(d_expert_buf) || !aligned16(d_expert_aux) ||
         !aligned16(d_send_buf) || !aligned16(d_send_aux))
         return FUSCO_ERR_INVALID_ARG;
-    if (L->N == 0) return FUSCO_OK;
 
     DispatchArgs a;
     a.x = (const u32x4 *)d_x;
@@ -1266,7 +1268,7 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
 {
     if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
     if (flags != 0) return FUSCO_ERR_UNSUPPORTED;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream);
     return launch_status();
@@ -1275,8 +1277,8 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
 int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, const float *d_w, float *d_partial,
                           void *d_out, int out_dtype, int32_t H, void *stream)
 {
-    if (!layout_ok(L) || !d_partial || !aligned16(d_partial)) return FUSCO_ERR_INVALID_ARG;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
+    if (!layout_ok(L) || (!d_partial && L->N > 0) || !aligned16(d_partial)) return FUSCO_ERR_INVALID_ARG;
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (L->k <= 8) {
@@ -1345,11 +1347,12 @@ static bool rank_layout_matches(const fusco_layout *L, const fusco_layout *Lr)
 int fusco_disaggregated_dispatch(const fusco_layout *L, const fusco_layout *Lr, const void *d_x, size_t row_bytes,
                                  void *d_stage_a, void *d_stage_b, void *d_expert_buf, void *stream)
 {
-    if (!rank_layout_matches(L, Lr) || !d_x || !d_stage_a || !d_stage_b || !d_expert_buf) return FUSCO_ERR_INVALID_ARG;
+    if (!rank_layout_matches(L, Lr)) return FUSCO_ERR_INVALID_ARG;
     if (row_bytes == 0 || row_bytes % 16 != 0 || row_bytes / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
+    if (L->N == 0) return FUSCO_OK;
+    if (!d_x || !d_stage_a || !d_stage_b || !d_expert_buf) return FUSCO_ERR_INVALID_ARG;
     if (!aligned16(d_x) || !aligned16(d_stage_a) || !aligned16(d_stage_b) || !aligned16(d_expert_buf))
         return FUSCO_ERR_INVALID_ARG;
-    if (L->N == 0) return FUSCO_OK;
     hipStream_t s = (hipStream_t)stream;
     const int C = (int)(row_bytes / 16);
     // 1) rearrange by destination device: one row per (token, expert) pair, device-major, token order
@@ -1365,11 +1368,10 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
                                 const float *d_w, void *d_stage_a, void *d_stage_b, void *d_out, int out_dtype,
                                 int32_t H, void *stream)
 {
-    if (!rank_layout_matches(L, Lr) || !d_stage_a || !d_stage_b) return FUSCO_ERR_INVALID_ARG;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H);
-    if (rc != FUSCO_OK) return rc;
-    if (!aligned16(d_stage_a) || !aligned16(d_stage_b)) return FUSCO_ERR_INVALID_ARG;
-    if (L->N == 0) return FUSCO_OK;
+    if (!rank_layout_matches(L, Lr)) return FUSCO_ERR_INVALID_ARG;
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
+    if (rc != FUSCO_OK || L->N == 0) return rc;
+    if (!d_stage_a || !d_stage_b || !aligned16(d_stage_a) || !aligned16(d_stage_b)) return FUSCO_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
     const size_t row_bytes = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
     // 3') expert order -> rank order, 2') exchange copy, 1') un-permute with the weighted sum

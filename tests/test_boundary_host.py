@@ -105,6 +105,15 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
     assert d(buf, (1 << 20) + 16, None, 0, buf, None, None, None, 0, None) == -1 # just above FUSCO_MAX_ROW_BYTES
     assert d(buf, 1 << 20, buf, 16, buf, buf, None, None, 0, None) == -1         # the two planes together are
+    # an empty layout takes NULL tensors (nothing is launched), sizes are still checked
+    L0 = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(L0), 0, k, E, D, base + (1 << 25), lib.fusco_layout_bytes(0, k, E, D)) == 0
+    assert lib.fusco_dispatch(ctypes.byref(L0), None, 64, None, 0, None, None, None, None, 3, None) == 0
+    assert lib.fusco_dispatch(ctypes.byref(L0), None, 40, None, 0, None, None, None, None, 0, None) == -1
+    assert lib.fusco_combine(ctypes.byref(L0), None, 0, None, None, 0, 64, 0, None) == 0
+    assert lib.fusco_combine(ctypes.byref(L0), None, 0, None, None, 0, 12, 0, None) == -1
+    assert lib.fusco_combine(ctypes.byref(L0), None, 5, None, None, 0, 64, 0, None) == -3
+    assert lib.fusco_combine_two_hop(ctypes.byref(L0), None, 0, None, None, None, 0, 64, None) == 0
     # combine
     c = lambda *a: lib.fusco_combine(ctypes.byref(L), *a)
     assert c(None, 0, buf, buf, 0, 64, 0, None) == -1

@@ -89,6 +89,22 @@ def test_plan_empty_input(fusco, oracle):
     assert got.exp_count.tolist() == [0] * 8 and got.send_count.tolist() == [0] * 2 and int(got.status[0]) == 0
 
 
+def test_movers_accept_an_empty_layout(fusco):
+    L, _ = gpu_plan(fusco, np.zeros((0, 4), dtype=np.int32), 8, 2)
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    eb = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    sb = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    for flags in (0, 2, 3, 4):
+        fusco.fusco_dispatch(L, x, eb, send_buf=sb, flags=flags)
+    out = torch.empty((0, 64), dtype=torch.bfloat16, device="cuda")
+    w = torch.empty((0, 4), dtype=torch.float32, device="cuda")
+    fusco.fusco_combine(L, eb, w, out)
+    fusco.fusco_combine_two_hop(L, eb, w, torch.empty((0, 64), dtype=torch.float32, device="cuda"), out)
+    torch.cuda.synchronize()
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_dispatch(L, torch.empty((0, 24), dtype=torch.uint8, device="cuda"), eb)   # row size still checked
+
+
 def test_plan_skewed_all_to_one_expert(fusco, oracle):
     A = np.zeros((5000, 1), dtype=np.int32) + 3
     L, got = gpu_plan(fusco, A, 8, 4)
