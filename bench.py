@@ -15,6 +15,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -29,7 +31,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=10.0, max_passes=64):
+def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=8.0, max_passes=64):
     """The CPU oracle, as it stands, on the same workload: plan + two-hop dispatch + fp64 combine,
     repeated until about min_seconds of CPU work have been timed."""
     import oracle
@@ -47,6 +49,33 @@ def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=10.0, max_passes=64):
             "sample": "%d of %d tokens of the %s workload, %d passes of plan + two-hop dispatch + fp64 combine "
                       "on one host thread, %.1f s" % (cfg.N, total_tokens, cfg.name, passes, dt),
             "host_cores_available": os.cpu_count()}
+
+
+def cpu_baseline_all_cores(cfg, total_tokens, A, w, xb, threads, min_seconds=5.0, max_passes=64):
+    """The same oracle functions with the independent rows of dispatch and combine handed to `threads` host
+    threads in contiguous ranges (its row-subset calls; the plan stays on one thread).  Results are the same
+    rows, only computed side by side."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
+    oracle.build()
+    slot_cuts = np.linspace(0, cfg.P, threads + 1).astype(np.int64)
+    tok_cuts = np.linspace(0, cfg.N, threads + 1).astype(np.int64)
+    passes, t0 = 0, time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        while True:
+            pl = oracle.plan(A, cfg.E, cfg.D)
+            parts = list(pool.map(lambda i: oracle.dispatch_rows(pl, xb, np.arange(slot_cuts[i], slot_cuts[i + 1])),
+                                  range(threads)))
+            eb = np.concatenate(parts)
+            list(pool.map(lambda i: oracle.combine_f64(eb, w, pl.pair_slot, np.arange(tok_cuts[i], tok_cuts[i + 1])),
+                          range(threads)))
+            passes += 1
+            dt = time.perf_counter() - t0
+            if dt >= min_seconds or passes >= max_passes:
+                break
+    return {"value": cfg.N * passes / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d tokens of the %s workload, %d passes; dispatch and combine rows split over %d host "
+                      "threads, plan on one, %.1f s" % (cfg.N, total_tokens, cfg.name, passes, threads, dt)}
 
 
 def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
@@ -365,6 +394,9 @@ def main() -> int:
         n = args.cpu_sample_tokens or cfg.N
         sub = cfg.with_tokens(min(n, cfg.N))
         result["cpu_baseline"] = cpu_baseline(sub, cfg.N, A[:sub.N], w[:sub.N], xb[:sub.N])
+        if cfg.payload == "bf16":
+            result["cpu_baseline_all_cores"] = cpu_baseline_all_cores(sub, cfg.N, A[:sub.N], w[:sub.N], xb[:sub.N],
+                                                                      min(16, os.cpu_count() or 1))
     print(json.dumps(result))
     return 0
 
