@@ -33,7 +33,7 @@ def _bits(t):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("name,compare_all", [("dsv3", True), ("qwen3", False), ("skewed", False)])
+@pytest.mark.parametrize("name,compare_all", [("tiny", True), ("dsv3", True), ("qwen3", False), ("skewed", False)])
 def test_full_size_path(fusco, oracle, name, compare_all):
     cfg = W.get_config(name)
     print("config", name, "N", cfg.N, "H", cfg.H, flush=True)
