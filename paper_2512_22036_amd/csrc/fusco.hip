@@ -22,7 +22,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWave = 64;
 constexpr int kPlanThreads = 1024;                      // 16 waves per planner workgroup
 constexpr int kPlanWaves = kPlanThreads / kWave;
-constexpr int kTilePairs = 2048;                        // (token, expert) pairs per planner tile
+constexpr int kTilePairs = 1024;                        // (token, expert) pairs per planner tile
 constexpr int kRounds = kTilePairs / kPlanThreads;      // 64-pair rounds per wave
 constexpr int kWaveChunk = kTilePairs / kPlanWaves;     // consecutive pairs owned by one wave
 constexpr int kMaxBins = FUSCO_MAX_E;
@@ -43,7 +43,7 @@ bool sizes_ok(int32_t N, int32_t k, int32_t E, int32_t D)
 
 // From this many tiles on, per-tile counts are first summed over chunks of tiles (one more small launch),
 // so that a placement workgroup reads about 2 * sqrt(tiles) rows of counts instead of one per tile.
-constexpr int kChunkMinTiles = 96;
+constexpr int kChunkMinTiles = 320;
 
 inline int tokens_per_tile(int k) { return kTilePairs / k; }
 inline int num_tiles(int N, int k)
@@ -105,7 +105,8 @@ __device__ __forceinline__ uint64_t same_key_lanes(int key, bool part, int nbits
     return m;
 }
 
-// n / d for the small operands of the planner (n < 2048 with d <= 64, or n < 1024 with d <= 1024)
+// n / d for the small operands of the planner (n < 2048 with d <= 64, or n < 1024 with d <= 1024; the
+// callers stay below: pair index in a tile < 1024 over k <= 64, expert id < 1024 over E / D)
 // through magic = ceil(2^20 / d): the error n * (magic * d - 2^20) / (d * 2^20) stays below 1 / d.
 __device__ __forceinline__ int div20(int n, uint32_t magic) { return (int)(((uint32_t)n * magic) >> 20); }
 

@@ -54,10 +54,11 @@ def assert_plan_equal(got, want):
 
 
 PLAN_SHAPES = [
-    # N, k, E, D, distinct experts per token
+    # N, k, E, D, distinct experts per token       (a planner tile holds 1024 pairs)
     (1, 1, 1, 1, True), (1, 8, 256, 8, True), (5, 2, 4, 2, True), (64, 2, 16, 4, True),
-    (256, 8, 256, 8, True),        # exactly one tile
-    (257, 8, 256, 8, True),        # one tile and one token
+    (128, 8, 256, 8, True),        # exactly one tile
+    (129, 8, 256, 8, True),        # one tile and one token
+    (256, 8, 256, 8, True), (257, 8, 256, 8, True),
     (1000, 8, 256, 8, True),       # several tiles, ragged tail
     (4096, 2, 16, 4, True), (3000, 8, 128, 16, True), (777, 6, 96, 12, True),
     (300, 64, 1024, 64, True),     # largest k and E
@@ -65,12 +66,13 @@ PLAN_SHAPES = [
     (900, 4, 64, 1, True),         # single device
     (1300, 5, 10, 5, False),       # repeated experts inside a token
     (2100, 7, 7, 7, False), (129, 33, 66, 2, True),
-    # many tiles: per-tile counts are summed over chunks of tiles first (from 96 tiles on)
-    (24320, 8, 256, 8, False),     # 95 tiles: the last size read tile by tile
-    (24321, 8, 256, 8, False),     # 96 tiles, the last one holding one token
-    (30011, 8, 64, 16, True),      # 118 tiles, ragged
-    (3200, 64, 1024, 1024, True),  # 100 tiles, more count columns than threads
-    (600000, 8, 32, 4, False),     # 2344 tiles, chunks of 64, last chunk ragged
+    # many tiles: from 320 tiles on, per-tile counts are first summed over chunks of tiles
+    (40832, 8, 256, 8, False),     # 319 tiles: the last size read tile by tile
+    (40833, 8, 256, 8, False),     # 320 tiles, the last one holding one token
+    (30011, 8, 64, 16, True),      # 235 tiles, ragged
+    (50011, 8, 64, 16, True),      # 391 tiles in chunks of 32, ragged
+    (5200, 64, 1024, 1024, True),  # 325 tiles, more count columns than threads
+    (600000, 8, 32, 4, False),     # 4688 tiles, chunks of 128, last chunk ragged
 ]
 
 
@@ -134,7 +136,7 @@ def test_plan_is_deterministic(fusco):
         assert torch.equal(L.mem, ref)
 
 
-@pytest.mark.parametrize("N", [700, 60000])          # one-level and chunked counts
+@pytest.mark.parametrize("N", [700, 90000])          # one-level and chunked counts (352 tiles)
 def test_plan_counts_invalid_ids(fusco, oracle, N):
     rng = np.random.default_rng(77)
     k, E, D = 4, 32, 4
