@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # profiles/bench_dsv3_hbm_traffic_pmc.txt: FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by what
 # the same counter reads for the 1 GiB plain-copy probe (1.99994 and 1.00000 KiB per count).
 MEASURED_TRAFFIC_BYTES = {
-    "dsv3": {"dispatch": 119476703 + 939524096, "combine": 941656807 + 117440512},
+    "dsv3": {"dispatch": 119480125 + 939524096, "combine": 941656208 + 117440512},
 }
 
 
@@ -294,20 +294,25 @@ def main() -> int:
     ms_per_step = wall * 1e3 / K
     tokens_per_s = cfg.N * K / wall
 
-    # per-kernel durations: the same K steps again with HIP events on the launch stream around every
-    # call (an event costs about 5 us of stream time, which is why they stay out of the region above)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    # per-kernel durations: the same K steps again, every call carrying a pair of HIP events that its own
+    # kernels record (start of the first, end of the last; fusco_probe_time_next_call).  Nothing is put into
+    # the stream between the kernels, so the steps run as in the region above; a pair of stream events
+    # around each call would add about 5 us of barriers to it.
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(K)]
+    for row in ev:
+        for e in row:
+            e.record()          # creates the HIP event
+    torch.cuda.synchronize()
     for i in range(K):
         sx, se, sy, so, kw = sets[i % len(sets)]
-        ev[i][0].record()
+        fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
         fusco.fusco_plan(L, d_A)
-        ev[i][1].record()
+        fusco.fusco_probe_time_next_call(ev[i][2], ev[i][3])
         fusco.fusco_dispatch(L, sx, se, **kw)
-        ev[i][2].record()
+        fusco.fusco_probe_time_next_call(ev[i][4], ev[i][5])
         fusco.fusco_combine(L, sy, d_w, so)
-        ev[i][3].record()
     torch.cuda.synchronize()
-    ms = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
+    ms = np.array([[ev[i][2 * j].elapsed_time(ev[i][2 * j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
     plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
 
     variants = None
@@ -374,7 +379,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
-                     "timing": "mean over a second pass of the same K steps with HIP events around each call"},
+                     "timing": "mean over a second pass of the same K steps; each call's kernels record their own "
+                               "start and end HIP events (no stream events between kernels)"},
         "kernels": kernels,
         "dispatch_plus_combine": {"ms": float(disp_ms + comb_ms), "tokens_per_s": cfg.N / ((disp_ms + comb_ms) * 1e-3),
                                   "GBps": both, "frac_of_peak": both / HBM_PEAK_GBS},

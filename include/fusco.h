@@ -265,6 +265,21 @@ int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t
                      int reads_per_group, int writes_per_group, int scatter, int write_through,
                      uint32_t *d_sink, void *stream);
 
+/*
+ * Measurement aid: kernel time without stream events between the kernels.  The next fusco_plan,
+ * fusco_dispatch (fused modes) or fusco_combine call made by the calling thread attaches the two HIP
+ * events (hipEvent_t passed as void*, created with timing enabled) to its own kernels: start_event
+ * is recorded when the call's first kernel begins, stop_event when its last kernel ends, both from
+ * the kernels' own dispatch timestamps.  hipEventElapsedTime(start, stop) after the stream has been
+ * synchronised is then the device time of that call, as a profiler's kernel trace reports it; a
+ * pair of hipEventRecord calls around the launch would add the cost of the barriers they put into
+ * the stream.  The arming is per thread and is used up by the first such call that launches
+ * kernels (a call that fails its argument checks or has an empty layout leaves it armed;
+ * FUSCO_DISPATCH_TWO_HOP uses it up without recording).  Events are not recorded into a stream
+ * that is being captured: do not arm before a captured call.
+ */
+int fusco_probe_time_next_call(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy", "fusco_probe_rows",
+           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.fusco_probe_time_next_call.restype = ctypes.c_int
+    lib.fusco_probe_time_next_call.argtypes = [vp, vp]
     lib.fusco_probe_rows.restype = ctypes.c_int
     lib.fusco_probe_rows.argtypes = [vp, u32, vp, u32, sz, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      vp, vp]
@@ -319,6 +321,15 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise FuscoError("dst is smaller than src")
     _check(load_library().fusco_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
            "fusco_probe_copy")
+
+
+def fusco_probe_time_next_call(start: torch.cuda.Event, stop: torch.cuda.Event) -> None:
+    """The next plan / dispatch / combine call of this thread records its own device time into the two events
+    (created with enable_timing=True and recorded once before, so that their HIP handles exist)."""
+    h0, h1 = int(start.cuda_event or 0), int(stop.cuda_event or 0)
+    if not h0 or not h1:
+        raise FuscoError("events must have been recorded once (torch creates the HIP event on first use)")
+    _check(load_library().fusco_probe_time_next_call(h0, h1), "fusco_probe_time_next_call")
 
 
 def fusco_probe_rows(src, dst, reads: int, writes: int, scatter: bool, write_through: bool = False,

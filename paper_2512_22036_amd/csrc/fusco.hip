@@ -8,6 +8,7 @@
 // are built around 16-byte coalesced global accesses, the planner around LDS counters and
 // wave64 ballots.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <stdint.h>
 #include <stdlib.h>
@@ -1029,11 +1030,33 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? FUSCO_OK : FUSCO_ERR_HIP;
 }
 
+// Events armed by fusco_probe_time_next_call for the calling thread (null when not armed), and their
+// hand-over to the call that consumes them.
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
+struct ArmedEvents {
+    hipEvent_t start, stop;
+    ArmedEvents() : start(g_time_start), stop(g_time_stop)
+    {
+        g_time_start = nullptr;
+        g_time_stop = nullptr;
+    }
+};
+
+// Kernel launch that can carry a start and a stop event of its own: hipExtLaunchKernelGGL records them
+// from the dispatch's own timestamps, without the barrier that a stream event puts between kernels.
+template <typename K, typename A>
+void launch(K kernel, dim3 grid, dim3 block, hipStream_t s, const A &a, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr)
+{
+    if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, a);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+}
+
 template <bool Y_BF16, bool OUT_BF16>
-void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s)
+void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
     const dim3 grid((unsigned)N, (unsigned)((a.C + threads - 1) / threads)), block((unsigned)threads);
-    hipLaunchKernelGGL((combine_kernel<Y_BF16, OUT_BF16, 1, 8>), grid, block, 0, s, a);
+    launch(combine_kernel<Y_BF16, OUT_BF16, 1, 8>, grid, block, s, a, e0, e1);
 }
 
 // dst[r] = src[index(r)] for n_rows destination rows of C chunks (see gather_rows_kernel)
@@ -1080,7 +1103,8 @@ int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_
 
 // out[t] = sum_j w[t, j] * y[pair_slot[t * k + j]] for N tokens; arguments already checked
 void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int y_dtype, const float *d_w,
-                    void *d_out, int out_dtype, int32_t H, hipStream_t s)
+                    void *d_out, int out_dtype, int32_t H, hipStream_t s, hipEvent_t e0 = nullptr,
+                    hipEvent_t e1 = nullptr)
 {
     CombineArgs a;
     a.y = (const u32x4 *)d_y;
@@ -1093,10 +1117,10 @@ void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int
     // one workgroup per token whenever the row fits 1024 threads
     int threads = round_up(a.C, kWave);
     if (threads > 1024) threads = 1024;
-    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, s);
-    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, s);
-    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, s);
-    else launch_combine<false, false>(a, N, threads, s);
+    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, s, e0, e1);
+    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, s, e0, e1);
+    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, s, e0, e1);
+    else launch_combine<false, false>(a, N, threads, s, e0, e1);
 }
 
 }   // namespace
@@ -1201,12 +1225,13 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
     a.pair_send_row = L->pair_send_row; a.slot_send_row = L->slot_send_row; a.pair_first = L->pair_first;
     a.status = L->status;
     hipStream_t s = (hipStream_t)stream;
+    const ArmedEvents ev;
     if (a.n_tiles == 1) {
-        hipLaunchKernelGGL(plan_place_kernel<true>, dim3(1), dim3(kPlanThreads), 0, s, a);
+        launch(plan_place_kernel<true>, dim3(1), dim3(kPlanThreads), s, a, ev.start, ev.stop);
     } else {
-        hipLaunchKernelGGL(plan_count_kernel, dim3(a.n_tiles), dim3(kPlanThreads), 0, s, a);
-        if (a.n_chunks > 0) hipLaunchKernelGGL(plan_chunk_kernel, dim3(a.n_chunks), dim3(kPlanThreads), 0, s, a);
-        hipLaunchKernelGGL(plan_place_kernel<false>, dim3(a.n_tiles), dim3(kPlanThreads), 0, s, a);
+        launch(plan_count_kernel, dim3(a.n_tiles), dim3(kPlanThreads), s, a, ev.start, nullptr);
+        if (a.n_chunks > 0) launch(plan_chunk_kernel, dim3(a.n_chunks), dim3(kPlanThreads), s, a);
+        launch(plan_place_kernel<false>, dim3(a.n_tiles), dim3(kPlanThreads), s, a, nullptr, ev.stop);
     }
     return launch_status();
 }
@@ -1249,10 +1274,12 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     const int segs = (Ct + threads * cpt - 1) / (threads * cpt);
     const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
     hipStream_t s = (hipStream_t)stream;
+    ArmedEvents ev;
+    if (two_hop) ev.start = ev.stop = nullptr;   // several kernels: armed events are dropped
     switch (cpt) {
-    case 1: hipLaunchKernelGGL(dispatch_kernel<1>, grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL(dispatch_kernel<2>, grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL(dispatch_kernel<4>, grid, block, 0, s, a); break;
+    case 1: launch(dispatch_kernel<1>, grid, block, s, a, ev.start, ev.stop); break;
+    case 2: launch(dispatch_kernel<2>, grid, block, s, a, ev.start, ev.stop); break;
+    default: launch(dispatch_kernel<4>, grid, block, s, a, ev.start, ev.stop); break;
     }
     if (two_hop) {
         // second hop: every row of the expert tensor is pulled from its token's row in the receive
@@ -1271,7 +1298,9 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
     if (flags != 0) return FUSCO_ERR_UNSUPPORTED;
     const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
     if (rc != FUSCO_OK || L->N == 0) return rc;
-    combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream);
+    const ArmedEvents ev;
+    combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream, ev.start,
+                   ev.stop);
     return launch_status();
 }
 
@@ -1485,6 +1514,14 @@ int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t
     else if (R == 1) hipLaunchKernelGGL((probe_rows_kernel<1, 8>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((probe_rows_kernel<8, 1>), grid, block, 0, s, a);
     return launch_status();
+}
+
+int fusco_probe_time_next_call(void *start_event, void *stop_event)
+{
+    if (!start_event || !stop_event) return FUSCO_ERR_INVALID_ARG;
+    g_time_start = (hipEvent_t)start_event;
+    g_time_stop = (hipEvent_t)stop_event;
+    return FUSCO_OK;
 }
 
 }   // extern "C"

@@ -173,6 +173,7 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_copy(buf, buf + 4, 64, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4096, 24, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4096, 0, None) == 0
+    assert lib.fusco_probe_time_next_call(None, buf) == -1 and lib.fusco_probe_time_next_call(buf, None) == -1
     # probe rows: unsupported shapes, bad sizes, missing buffers (nothing is launched on error)
     pr = lib.fusco_probe_rows
     assert pr(buf, 8, buf + 4096, 8, 64, 2, 1, 0, 0, None, None) == -1        # shape not offered

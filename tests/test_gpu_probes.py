@@ -90,3 +90,43 @@ def test_probe_rejects_bad_shapes(fusco):
         fusco.fusco_probe_rows(a, a, 3, 1, scatter=False)          # shape not offered
     with pytest.raises(fusco.FuscoError):
         fusco.fusco_probe_rows(a, None, 1, 0, scatter=False)       # read-only shape without a sink
+
+
+def test_call_timing_events(fusco):
+    """Armed events are recorded by the call's own kernels, are used up by one call, and change no result."""
+    rng = np.random.default_rng(5)
+    N, k, E, D, H = 3000, 4, 32, 4, 512
+    A = np.stack([rng.permutation(E)[:k] for _ in range(N)]).astype(np.int32)
+    d_A = torch.from_numpy(A).cuda()
+    L = fusco.Layout(N, k, E, D)
+    x = torch.randn((N, H), device="cuda").to(torch.bfloat16)
+    w = torch.full((N, k), 1.0 / k, device="cuda")
+    eb0 = torch.empty((N * k, H), dtype=torch.bfloat16, device="cuda")
+    out0 = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    fusco.fusco_plan(L, d_A)
+    ref_layout = L.mem.clone()
+    fusco.fusco_dispatch(L, x, eb0)
+    fusco.fusco_combine(L, eb0, w, out0)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    fresh = torch.cuda.Event(enable_timing=True)
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_probe_time_next_call(fresh, ev[0])      # never recorded: no HIP event behind it yet
+    for e in ev:
+        e.record()
+    torch.cuda.synchronize()
+    eb = torch.zeros_like(eb0)
+    out = torch.zeros_like(out0)
+    fusco.fusco_probe_time_next_call(ev[0], ev[1])
+    fusco.fusco_plan(L, d_A)                                # three kernels (12 tiles): first start, last end
+    fusco.fusco_probe_time_next_call(ev[2], ev[3])
+    fusco.fusco_dispatch(L, x, eb)
+    fusco.fusco_probe_time_next_call(ev[4], ev[5])
+    fusco.fusco_combine(L, eb, w, out)
+    fusco.fusco_combine(L, eb, w, out)                      # not armed any more: ordinary launch
+    torch.cuda.synchronize()
+    assert torch.equal(L.mem, ref_layout) and torch.equal(eb, eb0) and torch.equal(out, out0)
+    for i in range(0, 6, 2):
+        ms = ev[i].elapsed_time(ev[i + 1])
+        assert 0.0005 < ms < 5.0, (i, ms)
+    # the calls ran in stream order: plan ends before dispatch starts, dispatch before combine
+    assert ev[1].elapsed_time(ev[2]) >= 0.0 and ev[3].elapsed_time(ev[4]) >= 0.0
