@@ -319,6 +319,28 @@ def main() -> int:
     if not args.no_variants and cfg.payload == "bf16":
         variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
 
+    # decode-sized inputs (one planner tile): the same step with plan and dispatch in one launch
+    fused = None
+    if cfg.N <= 1024 // cfg.k and len(sets) == 1 and not args.graph:
+        def fused_step():
+            fusco.fusco_plan_dispatch(L, d_A, d_x, d_expert, **{k_: v for k_, v in dispatch_kwargs.items()})
+            fusco.fusco_combine(L, d_y, d_w, d_out)
+        want_layout, want_expert = L.mem.clone(), d_expert.clone()
+        d_expert.zero_()
+        for _ in range(args.warmup):
+            fused_step()
+        torch.cuda.synchronize()
+        if not (torch.equal(L.mem, want_layout) and torch.equal(d_expert, want_expert)):
+            print("bench.py: fused plan + dispatch differs from the two calls", file=sys.stderr)
+            return 1
+        t0 = time.perf_counter()
+        for _ in range(K):
+            fused_step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        fused = {"ms_per_step": dt * 1e3 / K, "tokens_per_s": cfg.N * K / dt,
+                 "launches": "fusco_plan_dispatch + fusco_combine"}
+
     ceilings = None
     if not args.no_ceilings and cfg.payload == "bf16":
         ceilings = measure_ceilings(fusco, torch, cfg, d_x, d_expert, d_out, max(10, K // 10))
@@ -388,6 +410,8 @@ def main() -> int:
         "launch": "one HIP graph replay per step" if args.graph else "three library calls per step",
         "buffer_sets": len(sets),
     }
+    if fused is not None:
+        result["fused_plan_dispatch_step"] = fused
     if ceilings is not None:
         result["ceilings"] = ceilings
     if variants is not None:

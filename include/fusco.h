@@ -138,6 +138,19 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                    void *d_send_aux, uint32_t flags, void *stream);
 
 /*
+ * fusco_plan followed by fusco_dispatch (FUSCO_DISPATCH_EXPERT only) in a single launch, for inputs
+ * that fit one planner tile: N <= floor(1024 / k) tokens (decode-sized batches, where a chain of
+ * dependent launches costs more than the work; the planner's cost is fixed and shows at small
+ * sizes, section 5.2).  Results are exactly those of the two calls: every descriptor array of *L is
+ * written as by fusco_plan (no scratch is needed), d_expert_buf / d_expert_aux as by fusco_dispatch.
+ * Arguments as in those two calls.  Returns FUSCO_ERR_UNSUPPORTED when the input needs more than
+ * one tile; the caller then makes the two calls.
+ */
+int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *d_x, size_t row_bytes,
+                        const void *d_x_aux, size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux,
+                        void *stream);
+
+/*
  * Weighted combine (reverse path of the shuffle; "combined through a weighted summation",
  * section 2.1):   out[t, :] = sum_{j=0..k-1} w[t, j] * y[pair_slot[t*k+j], :]
  * accumulated in fp32 with one fused multiply-add per term in ascending j from +0, then rounded
@@ -267,7 +280,7 @@ int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t
 
 /*
  * Measurement aid: kernel time without stream events between the kernels.  The next fusco_plan,
- * fusco_dispatch (fused modes) or fusco_combine call made by the calling thread attaches the two HIP
+ * fusco_dispatch (fused modes), fusco_plan_dispatch or fusco_combine call made by the calling thread attaches the two HIP
  * events (hipEvent_t passed as void*, created with timing enabled) to its own kernels: start_event
  * is recorded when the call's first kernel begins, stop_event when its last kernel ends, both from
  * the kernels' own dispatch timestamps.  hipEventElapsedTime(start, stop) after the stream has been

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
+           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_plan.argtypes = [ctypes.POINTER(_CLayout), vp, vp, sz, vp]
     lib.fusco_dispatch.restype = ctypes.c_int
     lib.fusco_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, sz, vp, sz, vp, vp, vp, vp, u32, vp]
+    lib.fusco_plan_dispatch.restype = ctypes.c_int
+    lib.fusco_plan_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, vp, sz, vp, sz, vp, vp, vp]
     lib.fusco_combine.restype = ctypes.c_int
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
@@ -208,6 +210,26 @@ def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.T
     _check(load_library().fusco_dispatch(ctypes.byref(layout.c), x.data_ptr(), rb, _ptr(x_aux), ab,
                                          _ptr(expert_buf), _ptr(expert_aux), _ptr(send_buf), _ptr(send_aux),
                                          flags, _stream(stream)), "fusco_dispatch")
+
+
+def fusco_plan_dispatch(layout: Layout, topk_idx: torch.Tensor, x: torch.Tensor, expert_buf: torch.Tensor,
+                        x_aux: Optional[torch.Tensor] = None, expert_aux: Optional[torch.Tensor] = None,
+                        stream=None) -> None:
+    """fusco_plan and fusco_dispatch (expert tensor only) in one launch; inputs of one planner tile only
+    (N * k <= 1024 with whole tokens), FuscoError otherwise."""
+    if (not topk_idx.is_cuda or topk_idx.dtype != torch.int32 or not topk_idx.is_contiguous()
+            or tuple(topk_idx.shape) != (layout.N, layout.k)):
+        raise FuscoError("topk_idx must be a contiguous int32 device tensor of shape [N, k]")
+    rb = _rows(x, "x", layout.N)
+    ab = _rows(x_aux, "x_aux", layout.N) if x_aux is not None else 0
+    _rows(expert_buf, "expert_buf", layout.P, rb)
+    if ab:
+        if expert_aux is None:
+            raise FuscoError("expert_aux is required")
+        _rows(expert_aux, "expert_aux", layout.P, ab)
+    _check(load_library().fusco_plan_dispatch(ctypes.byref(layout.c), topk_idx.data_ptr(), x.data_ptr(), rb,
+                                              _ptr(x_aux), ab, expert_buf.data_ptr(), _ptr(expert_aux),
+                                              _stream(stream)), "fusco_plan_dispatch")
 
 
 def _dtype_code(t: torch.Tensor, name: str) -> int:

@@ -225,6 +225,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunk_kernel(PlanArgs a)
 struct PlaceLds {
     int16_t tile_dev[kTilePairs];              // device of every pair, -1 for an invalid expert id
     int tile_row[kTilePairs];                  // send row of the pairs that are first appearances
+    int tile_slot[kTilePairs];                 // expert-major slot of every pair (kept for the fused dispatch)
     uint16_t wave_cnt[kPlanWaves][kMaxBins];   // per wave and key: running count, then prefix over waves
     int base[kMaxBins];                        // per key: pairs in earlier tiles, then the tile's global start
     int total[kMaxBins + 1];
@@ -237,9 +238,9 @@ struct PlaceLds {
 // of its key) + (pairs with that key in earlier tiles) + (earlier pairs with that key in this
 // tile).  Block 0 also writes the per-key counts and their exclusive prefix sum.
 template <bool SINGLE>
-__device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, const int (&key)[kRounds], int nb,
-                                            int hist_off, int32_t *count_out, int32_t *off_out,
-                                            int (&pos)[kRounds])
+__device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int tile, bool writer,
+                                            const int (&key)[kRounds], int nb, int hist_off, int32_t *count_out,
+                                            int32_t *off_out, int (&pos)[kRounds])
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int nbits = bits_for(nb);
@@ -281,7 +282,7 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         const int part = tid / nb_pad, b = tid - part * nb_pad;
         if (part < parts && b < nb) {
             const int32_t *h = a.tile_hist + hist_off + b;
-            const int me = blockIdx.x;
+            const int me = tile;
             int tot = 0, pre = 0;
             if (a.chunk_tiles == 0) {
 #pragma unroll 8
@@ -308,7 +309,7 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         }
     }
     __syncthreads();
-    if (blockIdx.x == 0)
+    if (writer && tile == 0)
         for (int b = tid; b < nb; b += kPlanThreads) count_out[b] = s.total[b];
 
     // exclusive prefix sum over the keys, by wave 0: each lane owns a run of consecutive keys
@@ -331,7 +332,7 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
         if (lane == kWave - 1) s.total[nb] = incl;
     }
     __syncthreads();
-    if (blockIdx.x == 0)
+    if (writer && tile == 0)
         for (int b = tid; b <= nb; b += kPlanThreads) off_out[b] = s.total[b];
 
     // per key: prefix of the per-wave counts, and the global position where the tile's run starts
@@ -351,13 +352,14 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, cons
     __syncthreads();
 }
 
-// Pass 2 (or the only pass when the whole input is one tile): writes every descriptor array.
+// Placement of one tile by one workgroup: pass 2 of the multi-tile planner, or the whole plan when the
+// input is a single tile.  A writer stores every descriptor array; a workgroup that is not a writer only
+// keeps the tile's slots in LDS (the fused plan + dispatch kernel runs the single-tile plan redundantly in
+// every workgroup and lets one of them write it out).
 template <bool SINGLE>
-__global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
+__device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int tile, bool writer)
 {
-    __shared__ PlaceLds s;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int tile = blockIdx.x;
     const int tok0 = tile * a.tpt;
     const int ntok = min(a.tpt, a.N - tok0);
     const int npairs = ntok > 0 ? ntok * a.k : 0;
@@ -383,11 +385,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 
     // level 2 receive side: expert-major slot of every pair
     int slot[kRounds];
-    rank_by_key<SINGLE>(s, a, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
+    rank_by_key<SINGLE>(s, a, tile, writer, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
-        if (p < npairs) {
+        s.tile_slot[p] = slot[r];
+        if (writer && p < npairs) {
             a.pair_slot[pair0 + p] = slot[r];
             if (slot[r] >= 0) {
                 a.slot_pair[slot[r]] = (int32_t)(pair0 + p);
@@ -395,6 +398,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
             }
         }
     }
+
+    if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
 
     // level 1: one send row per (token, device), taken at the device's first appearance
     const int dbits = bits_for(a.D);
@@ -408,12 +413,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         dkey[r] = jfirst[r] == p ? d : -1;
     }
     int row[kRounds];
-    rank_by_key<SINGLE>(s, a, dkey, a.D, a.E, a.send_count, a.send_off, row);
+    rank_by_key<SINGLE>(s, a, tile, writer, dkey, a.D, a.E, a.send_count, a.send_off, row);
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
         s.tile_row[p] = row[r];
-        if (p < npairs) {
+        if (writer && p < npairs) {
             a.pair_first[pair0 + p] = row[r] >= 0 ? 1 : 0;
             if (row[r] >= 0) a.send_src[row[r]] = tok0 + tl[r];
         }
@@ -424,7 +429,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
         const int p = wave * kWaveChunk + r * kWave + lane;
-        if (p >= npairs) continue;
+        if (!writer || p >= npairs) continue;
         int srow = -1;
         if (ekey[r] >= 0) {
             srow = s.tile_row[jfirst[r]];
@@ -433,7 +438,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         a.pair_send_row[pair0 + p] = srow;
     }
 
-    if (blockIdx.x == 0 && wave == 0) {
+    if (writer && tile == 0 && wave == 0) {
         int bad = 0;
         if constexpr (SINGLE) {
             bad = s.invalid;
@@ -446,6 +451,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
         }
         if (lane == 0) *a.status = bad;
     }
+}
+
+template <bool SINGLE>
+__global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
+{
+    __shared__ PlaceLds s;
+    place_tile<SINGLE>(s, a, blockIdx.x, true);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -521,6 +533,55 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
                 if (c < a.C) a.send_buf[(size_t)row * a.C + c] = v[i];
                 else if (c < Ct) a.send_aux[(size_t)row * a.Ca + (c - a.C)] = v[i];
             }
+        }
+    }
+}
+
+// Planner and dispatch in one launch for inputs of a single planner tile (decode-sized batches, where
+// three dependent launches cost more than the work): one workgroup per token, every workgroup works out the
+// whole plan in its own LDS (a few microseconds, all in parallel), workgroup 0 writes the descriptor
+// arrays, and each workgroup then moves its token's row to the slots it has just computed.  The row is
+// requested before the planning starts, so that its latency hides behind it.
+constexpr int kFusedPreload = 4;   // 16-byte chunks per thread held in registers across the planning
+
+__global__ __launch_bounds__(kPlanThreads) void plan_dispatch_kernel(PlanArgs a, DispatchArgs m)
+{
+    __shared__ PlaceLds s;
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;   // the grid has max(N, 1) workgroups
+    const int Ct = m.C + m.Ca;
+    u32x4 v[kFusedPreload];
+    if (t < a.N) {
+#pragma unroll
+        for (int i = 0; i < kFusedPreload; ++i) {
+            const int c = tid + i * kPlanThreads;
+            if (c < m.C) v[i] = load16_stream(m.x + (size_t)t * m.C + c);
+            else if (c < Ct) v[i] = load16_stream(m.x_aux + (size_t)t * m.Ca + (c - m.C));
+        }
+    }
+    place_tile<true>(s, a, 0, blockIdx.x == 0);
+    __syncthreads();
+    if (t >= a.N) return;
+    const int *slots = s.tile_slot + t * a.k;
+    for (int j = 0; j < a.k; ++j) {
+        const int slot = slots[j];
+        if (slot < 0) continue;
+#pragma unroll
+        for (int i = 0; i < kFusedPreload; ++i) {
+            const int c = tid + i * kPlanThreads;
+            if (c < m.C) m.expert_buf[(size_t)slot * m.C + c] = v[i];
+            else if (c < Ct) m.expert_aux[(size_t)slot * m.Ca + (c - m.C)] = v[i];
+        }
+    }
+    // rows longer than the preloaded part
+    for (int c = tid + kFusedPreload * kPlanThreads; c < Ct; c += kPlanThreads) {
+        const u32x4 u = c < m.C ? load16_stream(m.x + (size_t)t * m.C + c)
+                                : load16_stream(m.x_aux + (size_t)t * m.Ca + (c - m.C));
+        for (int j = 0; j < a.k; ++j) {
+            const int slot = slots[j];
+            if (slot < 0) continue;
+            if (c < m.C) m.expert_buf[(size_t)slot * m.C + c] = u;
+            else m.expert_aux[(size_t)slot * m.Ca + (c - m.C)] = u;
         }
     }
 }
@@ -1204,10 +1265,8 @@ static bool layout_ok(const fusco_layout *L)
            L->slot_token && L->send_src && L->pair_send_row && L->slot_send_row && L->pair_first && L->status;
 }
 
-int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size_t scratch_bytes, void *stream)
+static PlanArgs plan_args(const fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch)
 {
-    if (!layout_ok(L) || (!d_topk_idx && L->N > 0) || !d_scratch) return FUSCO_ERR_INVALID_ARG;
-    if (scratch_bytes < fusco_scratch_bytes(L->N, L->k, L->E, L->D)) return FUSCO_ERR_WORKSPACE;
     PlanArgs a;
     a.A = d_topk_idx;
     a.N = L->N; a.k = L->k; a.E = L->E; a.D = L->D; a.Eloc = L->E / L->D;
@@ -1216,7 +1275,7 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
     a.tpt = tokens_per_tile(L->k);
     a.n_tiles = num_tiles(L->N, L->k);
     a.stride = L->E + L->D + 1;
-    a.tile_hist = (int32_t *)d_scratch;
+    a.tile_hist = (int32_t *)d_scratch;   // unused (may be NULL) when the input is a single tile
     a.chunk_tiles = chunk_tiles_for(a.n_tiles);
     a.n_chunks = num_chunks(a.n_tiles);
     a.chunk_hist = a.tile_hist + (size_t)a.n_tiles * (size_t)a.stride;
@@ -1224,6 +1283,14 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
     a.pair_slot = L->pair_slot; a.slot_pair = L->slot_pair; a.slot_token = L->slot_token; a.send_src = L->send_src;
     a.pair_send_row = L->pair_send_row; a.slot_send_row = L->slot_send_row; a.pair_first = L->pair_first;
     a.status = L->status;
+    return a;
+}
+
+int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size_t scratch_bytes, void *stream)
+{
+    if (!layout_ok(L) || (!d_topk_idx && L->N > 0) || !d_scratch) return FUSCO_ERR_INVALID_ARG;
+    if (scratch_bytes < fusco_scratch_bytes(L->N, L->k, L->E, L->D)) return FUSCO_ERR_WORKSPACE;
+    const PlanArgs a = plan_args(L, d_topk_idx, d_scratch);
     hipStream_t s = (hipStream_t)stream;
     const ArmedEvents ev;
     if (a.n_tiles == 1) {
@@ -1233,6 +1300,37 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
         if (a.n_chunks > 0) launch(plan_chunk_kernel, dim3(a.n_chunks), dim3(kPlanThreads), s, a);
         launch(plan_place_kernel<false>, dim3(a.n_tiles), dim3(kPlanThreads), s, a, nullptr, ev.stop);
     }
+    return launch_status();
+}
+
+int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *d_x, size_t row_bytes,
+                        const void *d_x_aux, size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux,
+                        void *stream)
+{
+    if (!layout_ok(L) || (!d_topk_idx && L->N > 0)) return FUSCO_ERR_INVALID_ARG;
+    if (row_bytes == 0 || row_bytes % 16 != 0 || aux_row_bytes % 16 != 0) return FUSCO_ERR_INVALID_ARG;
+    if ((row_bytes + aux_row_bytes) / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
+    if (num_tiles(L->N, L->k) != 1) return FUSCO_ERR_UNSUPPORTED;
+    if (L->N > 0) {
+        if (!d_x || !d_expert_buf || (aux_row_bytes && (!d_x_aux || !d_expert_aux))) return FUSCO_ERR_INVALID_ARG;
+        if (!aligned16(d_x) || !aligned16(d_x_aux) || !aligned16(d_expert_buf) || !aligned16(d_expert_aux))
+            return FUSCO_ERR_INVALID_ARG;
+    }
+    const PlanArgs a = plan_args(L, d_topk_idx, nullptr);
+    DispatchArgs m;
+    m.x = (const u32x4 *)d_x; m.x_aux = (const u32x4 *)d_x_aux;
+    m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
+    m.send_buf = nullptr; m.send_aux = nullptr;
+    m.pair_slot = L->pair_slot; m.pair_send_row = L->pair_send_row; m.pair_first = L->pair_first;
+    m.k = L->k;
+    m.C = (int32_t)(row_bytes / 16); m.Ca = (int32_t)(aux_row_bytes / 16);
+    m.write_expert = 1; m.write_wire = 0;
+    const ArmedEvents ev;
+    const dim3 grid((unsigned)(L->N > 0 ? L->N : 1)), block(kPlanThreads);
+    if (ev.start || ev.stop)
+        hipExtLaunchKernelGGL(plan_dispatch_kernel, grid, block, 0, (hipStream_t)stream, ev.start, ev.stop, 0, a, m);
+    else
+        hipLaunchKernelGGL(plan_dispatch_kernel, grid, block, 0, (hipStream_t)stream, a, m);
     return launch_status();
 }
 

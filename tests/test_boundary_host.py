@@ -105,6 +105,17 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
     assert d(buf, (1 << 20) + 16, None, 0, buf, None, None, None, 0, None) == -1 # just above FUSCO_MAX_ROW_BYTES
     assert d(buf, 1 << 20, buf, 16, buf, buf, None, None, 0, None) == -1         # the two planes together are
+    # fused plan + dispatch
+    pd = lambda *a: lib.fusco_plan_dispatch(ctypes.byref(L), *a)
+    assert pd(None, buf, 64, None, 0, buf, None, None) == -1                     # no routing
+    assert pd(buf, None, 64, None, 0, buf, None, None) == -1                     # no x
+    assert pd(buf, buf, 64, None, 0, None, None, None) == -1                     # no expert tensor
+    assert pd(buf, buf, 40, None, 0, buf, None, None) == -1                      # row size
+    assert pd(buf, buf, 64, None, 16, buf, None, None) == -1                     # aux plane without tensors
+    assert pd(buf, buf + 8, 64, None, 0, buf, None, None) == -1                  # misaligned
+    Lbig = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(Lbig), 1025, 1, E, D, base + (1 << 26), lib.fusco_layout_bytes(1025, 1, E, D)) == 0
+    assert lib.fusco_plan_dispatch(ctypes.byref(Lbig), buf, buf, 64, None, 0, buf, None, None) == -3   # two tiles
     # an empty layout takes NULL tensors (nothing is launched), sizes are still checked
     L0 = _CLayout()
     assert lib.fusco_layout_bind(ctypes.byref(L0), 0, k, E, D, base + (1 << 25), lib.fusco_layout_bytes(0, k, E, D)) == 0

@@ -336,6 +336,74 @@ def test_decode_fp8_config(fusco, oracle):
     _combine_case(fusco, oracle, A, cfg.E, cfg.D, yb, w, torch.float32)
 
 
+FUSED_SHAPES = [
+    # N, k, E, D, row_bytes, aux_row_bytes, distinct       (one planner tile: N <= 1024 // k)
+    (1, 1, 1, 1, 16, 0, True), (128, 8, 256, 64, 7168, 224, True), (128, 8, 256, 8, 14336, 0, True),
+    (1024, 1, 8, 4, 48, 16, True), (16, 64, 1024, 64, 4096, 0, True), (31, 33, 66, 2, 16 * 129, 0, True),
+    (100, 5, 10, 5, 16 * 37, 0, False),                       # repeated experts inside a token
+    (3, 2, 4, 2, 16 * 5000, 16 * 9, True),                    # row longer than the part held in registers
+    (2, 2, 4, 2, 1 << 20, 0, True),                           # the largest row
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", FUSED_SHAPES)
+def test_fused_plan_dispatch_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, aux_bytes, distinct):
+    rng = np.random.default_rng(N * 7 + k + row_bytes)
+    A = random_topk(rng, N, k, E, distinct)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    xa = rng.integers(0, 256, size=(N, aux_bytes), dtype=np.uint8) if aux_bytes else None
+    want = oracle.plan(A, E, D)
+    L = fusco.Layout(N, k, E, D)
+    L.mem.fill_(0x7B)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    ea = torch.full((L.P, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda") if aux_bytes else None
+    fusco.fusco_plan_dispatch(L, dev(A), dev(x), eb, x_aux=dev(xa) if aux_bytes else None, expert_aux=ea)
+    torch.cuda.synchronize()
+    assert_plan_equal(L.to_host(), want)
+    if aux_bytes:
+        _, expert_want, _, eaux_want = oracle.dispatch(want, x, xa)
+        assert np.array_equal(ea.cpu().numpy(), eaux_want)
+    else:
+        _, expert_want = oracle.dispatch(want, x)
+    assert np.array_equal(eb.cpu().numpy(), expert_want)
+
+
+def test_fused_plan_dispatch_edge_cases(fusco, oracle):
+    # empty input: the plan of nothing is still written
+    L = fusco.Layout(0, 4, 8, 2)
+    L.mem.fill_(0x7B)
+    fusco.fusco_plan_dispatch(L, torch.empty((0, 4), dtype=torch.int32, device="cuda"),
+                              torch.empty((0, 64), dtype=torch.uint8, device="cuda"),
+                              torch.empty((0, 64), dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    got = L.to_host()
+    assert got.exp_off.tolist() == [0] * 9 and got.send_off.tolist() == [0] * 3 and int(got.status[0]) == 0
+    # invalid ids are counted and their rows skipped, as by the two separate calls
+    rng = np.random.default_rng(3)
+    N, k, E, D = 60, 4, 32, 4
+    A = random_topk(rng, N, k, E).reshape(-1)
+    A[[5, 77, 200]] = [E, -1, 1000]
+    A = A.reshape(N, k)
+    x = rng.integers(0, 256, size=(N, 256), dtype=np.uint8)
+    L1, L2 = fusco.Layout(N, k, E, D), fusco.Layout(N, k, E, D)
+    L1.mem.fill_(0x7B)          # same stale bytes wherever neither path writes (unassigned slots, rows past U)
+    L2.mem.fill_(0x7B)
+    e1 = torch.full((N * k, 256), 0xEE, dtype=torch.uint8, device="cuda")
+    e2 = torch.full((N * k, 256), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_plan_dispatch(L1, dev(A), dev(x), e1)
+    fusco.fusco_plan(L2, dev(A))
+    fusco.fusco_dispatch(L2, dev(x), e2)
+    torch.cuda.synchronize()
+    assert int(L1.array("status").item()) == 3
+    assert torch.equal(L1.mem, L2.mem) and torch.equal(e1, e2)
+    # more than one tile: refused, nothing launched
+    Lb = fusco.Layout(129, 8, 256, 8)
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_plan_dispatch(Lb, torch.zeros((129, 8), dtype=torch.int32, device="cuda"),
+                                  torch.zeros((129, 64), dtype=torch.uint8, device="cuda"),
+                                  torch.zeros((129 * 8, 64), dtype=torch.uint8, device="cuda"))
+
+
 def test_binding_rejects_wrong_shapes(fusco):
     L = fusco.Layout(16, 2, 4, 2)
     x = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
