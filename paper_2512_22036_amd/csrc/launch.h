@@ -1,0 +1,130 @@
+// Host side: argument checks shared by the entry points, kernel launch helpers, per-call timing events.
+#ifndef FUSCO_CSRC_LAUNCH_H
+#define FUSCO_CSRC_LAUNCH_H
+
+#include "common.h"
+#include "planner.h"
+#include "movers.h"
+#include "segments.h"
+#include "probes.h"
+
+namespace {
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// odd multiplier close to frac * n that shares no factor with n: i -> i * mul mod n is a bijection of
+// [0, n) that sends neighbours far apart
+uint32_t coprime_near(uint32_t n, double frac)
+{
+    if (n < 3) return 1u;
+    uint32_t m = (uint32_t)((double)n * frac) | 1u;
+    for (;; m += 2) {
+        uint32_t x = n, y = m % n;
+        while (y) { const uint32_t r = x % y; x = y; y = r; }
+        if (x == 1 && m % n != 0) return m % n;
+    }
+}
+
+int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? FUSCO_OK : FUSCO_ERR_HIP;
+}
+
+// Events armed by fusco_probe_time_next_call for the calling thread (null when not armed), and their
+// hand-over to the call that consumes them.
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
+struct ArmedEvents {
+    hipEvent_t start, stop;
+    ArmedEvents() : start(g_time_start), stop(g_time_stop)
+    {
+        g_time_start = nullptr;
+        g_time_stop = nullptr;
+    }
+};
+
+// Kernel launch that can carry a start and a stop event of its own: hipExtLaunchKernelGGL records them
+// from the dispatch's own timestamps, without the barrier that a stream event puts between kernels.
+template <typename K, typename A>
+void launch(K kernel, dim3 grid, dim3 block, hipStream_t s, const A &a, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr)
+{
+    if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, a);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
+}
+
+template <bool Y_BF16, bool OUT_BF16>
+void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+{
+    const dim3 grid((unsigned)N, (unsigned)((a.C + threads - 1) / threads)), block((unsigned)threads);
+    launch(combine_kernel<Y_BF16, OUT_BF16, 1, 8>, grid, block, s, a, e0, e1);
+}
+
+// dst[r] = src[index(r)] for n_rows destination rows of C chunks (see gather_rows_kernel)
+template <bool STREAM_LOAD>
+void launch_gather(const void *src, void *dst, const int32_t *idx1, const int32_t *idx2, const int32_t *n_rows_dev,
+                   int n_rows, int C, hipStream_t s)
+{
+    if (n_rows <= 0 || C <= 0) return;
+    GatherArgs a;
+    a.src = (const u32x4 *)src; a.dst = (u32x4 *)dst;
+    a.idx1 = idx1; a.idx2 = idx2; a.n_rows_dev = n_rows_dev; a.C = C;
+    const int cpt = C >= 512 ? 4 : (C >= 128 ? 2 : 1);
+    int threads = round_up((C + cpt - 1) / cpt, kWave);
+    if (threads > 256) threads = 256;
+    const int segs = (C + threads * cpt - 1) / (threads * cpt);
+    const dim3 grid((unsigned)n_rows, (unsigned)segs), block((unsigned)threads);
+    switch (cpt) {
+    case 1: hipLaunchKernelGGL((gather_rows_kernel<1, STREAM_LOAD>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((gather_rows_kernel<2, STREAM_LOAD>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gather_rows_kernel<4, STREAM_LOAD>), grid, block, 0, s, a); break;
+    }
+}
+
+void launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
+{
+    const size_t n = bytes / 16;
+    if (n == 0) return;
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (u32x4 *)dst,
+                       (const u32x4 *)src, n);
+}
+
+// `empty`: the layout has no tokens, so the tensors hold no rows and may be NULL
+int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_out, int out_dtype, int32_t H,
+                  bool empty)
+{
+    if (H <= 0 || (!empty && (!d_y || !d_w || !d_out))) return FUSCO_ERR_INVALID_ARG;
+    if ((y_dtype != FUSCO_BF16 && y_dtype != FUSCO_F32) || (out_dtype != FUSCO_BF16 && out_dtype != FUSCO_F32))
+        return FUSCO_ERR_UNSUPPORTED;
+    const size_t y_row = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
+    if (y_row % 16 != 0 || y_row / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
+    if (!aligned16(d_y) || !aligned16(d_out) || ((uintptr_t)d_w & 3u)) return FUSCO_ERR_INVALID_ARG;
+    return FUSCO_OK;
+}
+
+// out[t] = sum_j w[t, j] * y[pair_slot[t * k + j]] for N tokens; arguments already checked
+void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int y_dtype, const float *d_w,
+                    void *d_out, int out_dtype, int32_t H, hipStream_t s, hipEvent_t e0 = nullptr,
+                    hipEvent_t e1 = nullptr)
+{
+    CombineArgs a;
+    a.y = (const u32x4 *)d_y;
+    a.w = d_w;
+    a.out = d_out;
+    a.pair_slot = pair_slot;
+    a.k = k;
+    a.pair_send_row = nullptr; a.send_src = nullptr; a.n_rows_dev = nullptr;
+    a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
+    // one workgroup per token whenever the row fits 1024 threads
+    int threads = round_up(a.C, kWave);
+    if (threads > 1024) threads = 1024;
+    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, s, e0, e1);
+    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, s, e0, e1);
+    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, s, e0, e1);
+    else launch_combine<false, false>(a, N, threads, s, e0, e1);
+}
+
+}   // namespace
+
+#endif

@@ -1,0 +1,447 @@
+// Mover kernels: fused gather-pack (dispatch), weighted combine, their two-hop and staged variants.
+#ifndef FUSCO_CSRC_MOVERS_H
+#define FUSCO_CSRC_MOVERS_H
+
+#include "common.h"
+#include "planner.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Movers.  Both give one workgroup to one token, because HBM rewards long bursts: a row is
+// fetched or written whole by neighbouring waves of one compute unit within a short time.
+// Measured on MI355X at 14 KiB rows: scattered row reads reach the streaming read rate, scattered
+// row writes do not (about 5.2 of 6.9 TB/s), so the movers keep the scattered side of dispatch
+// as short as possible (plain cached stores, several chunks per thread in flight).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ u32x4 load16_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// 16-byte / 8-byte stores that go to memory at system scope instead of lingering in the L2:
+// used for the token-ordered output of combine, which is never read again by this kernel.
+// The s_nop supplies the wait states gfx9 needs between a store of more than 8 bytes and a
+// following VALU write to its data registers; the compiler adds them for its own stores but
+// cannot see into this statement.
+__device__ __forceinline__ void store16_through(u32x4 *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store8_through(u32x2 *p, u32x2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+
+// Dispatch: the row is held in registers between the single read and the k (+ wire) writes.
+// Slot lookups depend only on blockIdx, so they are scalar loads.
+struct DispatchArgs {
+    const u32x4 *x, *x_aux;
+    u32x4 *expert_buf, *expert_aux, *send_buf, *send_aux;
+    const int32_t *pair_slot, *pair_send_row;
+    const uint8_t *pair_first;
+    int32_t k;
+    int32_t C, Ca;   // 16-byte chunks per row in the main and in the aux plane
+    int32_t write_expert, write_wire;
+};
+
+template <int CPT>
+__global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
+{
+    const int t = blockIdx.x;
+    const int Ct = a.C + a.Ca;
+    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    u32x4 v[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c < a.C) v[i] = load16_stream(a.x + (size_t)t * a.C + c);
+        else if (c < Ct) v[i] = load16_stream(a.x_aux + (size_t)t * a.Ca + (c - a.C));
+    }
+    const int32_t *slots = a.pair_slot + (size_t)t * a.k;
+    if (a.write_expert) {
+        for (int j = 0; j < a.k; ++j) {
+            const int slot = slots[j];
+            if (slot < 0) continue;
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int c = c0 + i * blockDim.x;
+                if (c < a.C) a.expert_buf[(size_t)slot * a.C + c] = v[i];
+                else if (c < Ct) a.expert_aux[(size_t)slot * a.Ca + (c - a.C)] = v[i];
+            }
+        }
+    }
+    if (a.write_wire) {
+        const int32_t *rows = a.pair_send_row + (size_t)t * a.k;
+        const uint8_t *first = a.pair_first + (size_t)t * a.k;
+        for (int j = 0; j < a.k; ++j) {
+            if (!first[j]) continue;
+            const int row = rows[j];
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                const int c = c0 + i * blockDim.x;
+                if (c < a.C) a.send_buf[(size_t)row * a.C + c] = v[i];
+                else if (c < Ct) a.send_aux[(size_t)row * a.Ca + (c - a.C)] = v[i];
+            }
+        }
+    }
+}
+
+// Planner and dispatch in one launch for inputs of a single planner tile (decode-sized batches, where
+// three dependent launches cost more than the work): one workgroup per token, every workgroup works out the
+// whole plan in its own LDS (a few microseconds, all in parallel), workgroup 0 writes the descriptor
+// arrays, and each workgroup then moves its token's row to the slots it has just computed.  The row is
+// requested before the planning starts, so that its latency hides behind it.
+constexpr int kFusedPreload = 4;   // 16-byte chunks per thread held in registers across the planning
+
+__global__ __launch_bounds__(kPlanThreads) void plan_dispatch_kernel(PlanArgs a, DispatchArgs m)
+{
+    __shared__ PlaceLds s;
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;   // the grid has max(N, 1) workgroups
+    const int Ct = m.C + m.Ca;
+    u32x4 v[kFusedPreload];
+    if (t < a.N) {
+#pragma unroll
+        for (int i = 0; i < kFusedPreload; ++i) {
+            const int c = tid + i * kPlanThreads;
+            if (c < m.C) v[i] = load16_stream(m.x + (size_t)t * m.C + c);
+            else if (c < Ct) v[i] = load16_stream(m.x_aux + (size_t)t * m.Ca + (c - m.C));
+        }
+    }
+    place_tile<true>(s, a, 0, blockIdx.x == 0);
+    __syncthreads();
+    if (t >= a.N) return;
+    const int *slots = s.tile_slot + t * a.k;
+    for (int j = 0; j < a.k; ++j) {
+        const int slot = slots[j];
+        if (slot < 0) continue;
+#pragma unroll
+        for (int i = 0; i < kFusedPreload; ++i) {
+            const int c = tid + i * kPlanThreads;
+            if (c < m.C) m.expert_buf[(size_t)slot * m.C + c] = v[i];
+            else if (c < Ct) m.expert_aux[(size_t)slot * m.Ca + (c - m.C)] = v[i];
+        }
+    }
+    // rows longer than the preloaded part
+    for (int c = tid + kFusedPreload * kPlanThreads; c < Ct; c += kPlanThreads) {
+        const u32x4 u = c < m.C ? load16_stream(m.x + (size_t)t * m.C + c)
+                                : load16_stream(m.x_aux + (size_t)t * m.Ca + (c - m.C));
+        for (int j = 0; j < a.k; ++j) {
+            const int slot = slots[j];
+            if (slot < 0) continue;
+            if (c < m.C) m.expert_buf[(size_t)slot * m.C + c] = u;
+            else m.expert_aux[(size_t)slot * m.Ca + (c - m.C)] = u;
+        }
+    }
+}
+
+// Combine: every thread owns CPT 16-byte chunks of the output row, pulls the matching chunks of
+// the token's k rows (JU rows in flight at a time) and accumulates in fp32 with one fused
+// multiply-add per term in ascending j.
+struct CombineArgs {
+    const u32x4 *y;
+    const float *w;
+    void *out;
+    const int32_t *pair_slot;
+    int32_t k;
+    int32_t C;   // 16-byte chunks per y row
+    // per-send-row mode (level 2 reversed): one workgroup per send row, only the token's entries on that row
+    const int32_t *pair_send_row, *send_src, *n_rows_dev;
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+
+// fp32 -> bfloat16 bits, round to nearest even, NaN kept quiet
+__device__ __forceinline__ uint32_t to_bf16(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <bool Y_BF16, bool OUT_BF16, int CPT, int JU, bool PER_SEND_ROW = false>
+__global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
+{
+    constexpr int EPC = Y_BF16 ? 8 : 4;   // elements per 16-byte chunk of y
+    // last row first: when combine follows dispatch, the rows written last are the ones still in
+    // the memory-side cache
+    const int r = gridDim.x - 1 - blockIdx.x;   // token, or send row in the per-send-row mode
+    int t = r;
+    if constexpr (PER_SEND_ROW) {
+        if (r >= *a.n_rows_dev) return;
+        t = a.send_src[r];
+    }
+    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    const int32_t *slots = a.pair_slot + (size_t)t * a.k;
+    const float *wt = a.w + (size_t)t * a.k;
+
+    float acc[CPT][EPC];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i)
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[i][e] = 0.0f;
+
+    for (int j0 = 0; j0 < a.k; j0 += JU) {
+        u32x4 v[JU][CPT];
+        float wj[JU];
+        bool on[JU];
+#pragma unroll
+        for (int jj = 0; jj < JU; ++jj) {
+            const int j = j0 + jj;
+            on[jj] = false;
+            if (j < a.k) {
+                const int slot = slots[j];
+                wj[jj] = wt[j];
+                bool take = slot >= 0;
+                if constexpr (PER_SEND_ROW) take = take && a.pair_send_row[(size_t)t * a.k + j] == r;
+                if (take) {
+                    on[jj] = true;
+#pragma unroll
+                    for (int i = 0; i < CPT; ++i) {
+                        const int c = c0 + i * blockDim.x;
+                        if (c < a.C) v[jj][i] = load16_stream(a.y + (size_t)slot * a.C + c);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < JU; ++jj) {
+            if (!on[jj]) continue;
+#pragma unroll
+            for (int i = 0; i < CPT; ++i) {
+                if constexpr (Y_BF16) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc[i][2 * q] = __builtin_fmaf(wj[jj], bf16_lo(v[jj][i][q]), acc[i][2 * q]);
+                        acc[i][2 * q + 1] = __builtin_fmaf(wj[jj], bf16_hi(v[jj][i][q]), acc[i][2 * q + 1]);
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        acc[i][q] = __builtin_fmaf(wj[jj], __uint_as_float(v[jj][i][q]), acc[i][q]);
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c >= a.C) continue;
+        const size_t e0 = ((size_t)r * a.C + c) * EPC;   // first output element of this chunk
+        if constexpr (OUT_BF16) {
+            uint32_t pk[EPC / 2];
+#pragma unroll
+            for (int q = 0; q < EPC / 2; ++q) pk[q] = to_bf16(acc[i][2 * q]) | (to_bf16(acc[i][2 * q + 1]) << 16);
+            if constexpr (Y_BF16) {
+                u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+                store16_through((u32x4 *)((uint16_t *)a.out + e0), o);
+            } else {
+                u32x2 o = {pk[0], pk[1]};
+                store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < EPC / 4; ++h) {
+                u32x4 o = {__float_as_uint(acc[i][4 * h]), __float_as_uint(acc[i][4 * h + 1]),
+                           __float_as_uint(acc[i][4 * h + 2]), __float_as_uint(acc[i][4 * h + 3])};
+                store16_through((u32x4 *)((float *)a.out + e0) + h, o);
+            }
+        }
+    }
+}
+
+// Two-hop combine for k <= 8 in one pass: the token's k source chunks are loaded once, the partial
+// sum of every destination device is formed (same operation order as the two-kernel path: fused
+// multiply-adds in ascending j inside a device, then plain additions of the partial sums in order
+// of first appearance), stored to the device's partial row, and added to the token's output.
+struct TwoHopArgs {
+    const u32x4 *y;
+    const float *w;
+    float *partial;
+    void *out;
+    const int32_t *pair_slot, *pair_send_row;
+    const uint8_t *pair_first;
+    int32_t k;
+    int32_t C;   // 16-byte chunks per y row
+};
+
+template <bool Y_BF16, bool OUT_BF16>
+__global__ __launch_bounds__(1024) void combine_two_hop_kernel(TwoHopArgs a)
+{
+    constexpr int EPC = Y_BF16 ? 8 : 4;
+    constexpr int KMAX = 8;
+    const int t = gridDim.x - 1 - blockIdx.x;
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    const int32_t *slots = a.pair_slot + (size_t)t * a.k;
+    const int32_t *rows = a.pair_send_row + (size_t)t * a.k;
+    const uint8_t *first = a.pair_first + (size_t)t * a.k;
+    const float *wt = a.w + (size_t)t * a.k;
+
+    u32x4 v[KMAX];
+    int row[KMAX];
+    float wj[KMAX];
+    bool on[KMAX], lead[KMAX];
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+        on[j] = false;
+        lead[j] = false;
+        row[j] = -1;
+        if (j < a.k) {
+            const int slot = slots[j];
+            row[j] = rows[j];
+            wj[j] = wt[j];
+            lead[j] = first[j];
+            if (slot >= 0) {
+                on[j] = true;
+                v[j] = load16_stream(a.y + (size_t)slot * a.C + c);
+            }
+        }
+    }
+    float total[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) total[e] = 0.0f;
+#pragma unroll
+    for (int f = 0; f < KMAX; ++f) {
+        if (!lead[f]) continue;
+        float acc[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) acc[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < KMAX; ++j) {
+            if (!on[j] || row[j] != row[f]) continue;
+            if constexpr (Y_BF16) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc[2 * q] = __builtin_fmaf(wj[j], bf16_lo(v[j][q]), acc[2 * q]);
+                    acc[2 * q + 1] = __builtin_fmaf(wj[j], bf16_hi(v[j][q]), acc[2 * q + 1]);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = __builtin_fmaf(wj[j], __uint_as_float(v[j][q]), acc[q]);
+            }
+        }
+        u32x4 *prow = (u32x4 *)(a.partial + ((size_t)row[f] * a.C + c) * EPC);
+#pragma unroll
+        for (int h = 0; h < EPC / 4; ++h) {
+            const u32x4 o = {__float_as_uint(acc[4 * h]), __float_as_uint(acc[4 * h + 1]),
+                             __float_as_uint(acc[4 * h + 2]), __float_as_uint(acc[4 * h + 3])};
+            prow[h] = o;
+        }
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) total[e] = total[e] + acc[e];
+    }
+    const size_t e0 = ((size_t)t * a.C + c) * EPC;
+    if constexpr (OUT_BF16) {
+        uint32_t pk[EPC / 2];
+#pragma unroll
+        for (int q = 0; q < EPC / 2; ++q) pk[q] = to_bf16(total[2 * q]) | (to_bf16(total[2 * q + 1]) << 16);
+        if constexpr (Y_BF16) {
+            const u32x4 o = {pk[0], pk[1], pk[2], pk[3]};
+            store16_through((u32x4 *)((uint16_t *)a.out + e0), o);
+        } else {
+            const u32x2 o = {pk[0], pk[1]};
+            store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < EPC / 4; ++h) {
+            const u32x4 o = {__float_as_uint(total[4 * h]), __float_as_uint(total[4 * h + 1]),
+                             __float_as_uint(total[4 * h + 2]), __float_as_uint(total[4 * h + 3])};
+            store16_through((u32x4 *)((float *)a.out + e0) + h, o);
+        }
+    }
+}
+
+// Level 1 reversed: out[t] = sum of the token's partial rows (fp32, one per destination device),
+// plain additions from +0 in the order in which the devices first appear among the token's entries.
+struct SumPartialsArgs {
+    const u32x4 *partial;   // [send rows, C] chunks of 4 floats
+    void *out;
+    const int32_t *pair_send_row;
+    const uint8_t *pair_first;
+    int32_t k;
+    int32_t C;              // 16-byte chunks (4 floats) per partial row
+};
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(1024) void sum_partials_kernel(SumPartialsArgs a)
+{
+    const int t = gridDim.x - 1 - blockIdx.x;
+    const int c = blockIdx.y * blockDim.x + threadIdx.x;
+    if (c >= a.C) return;
+    const int32_t *rows = a.pair_send_row + (size_t)t * a.k;
+    const uint8_t *first = a.pair_first + (size_t)t * a.k;
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int j0 = 0; j0 < a.k; j0 += 8) {
+        u32x4 v[8];
+        bool on[8];
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            const int j = j0 + jj;
+            on[jj] = j < a.k && first[j];
+            if (on[jj]) v[jj] = load16_stream(a.partial + (size_t)rows[j] * a.C + c);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            if (!on[jj]) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = acc[q] + __uint_as_float(v[jj][q]);
+        }
+    }
+    const size_t e0 = ((size_t)t * a.C + c) * 4;
+    if constexpr (OUT_BF16) {
+        u32x2 o = {to_bf16(acc[0]) | (to_bf16(acc[1]) << 16), to_bf16(acc[2]) | (to_bf16(acc[3]) << 16)};
+        store8_through((u32x2 *)((uint16_t *)a.out + e0), o);
+    } else {
+        u32x4 o = {__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]), __float_as_uint(acc[3])};
+        store16_through((u32x4 *)((float *)a.out + e0), o);
+    }
+}
+
+// Row gather in destination order: dst[r] = src[idx2 ? idx2[idx1[r]] : idx1[r]] for r < n_rows, one
+// workgroup column per destination row.  n_rows_dev, when set, is a device-resident row count that
+// caps n_rows (data-dependent lengths such as U).  Used by the two-hop dispatch (second hop) and by
+// the disaggregated baseline, whose every stage is such a pass over the whole buffer.
+struct GatherArgs {
+    const u32x4 *src;
+    u32x4 *dst;
+    const int32_t *idx1, *idx2;
+    const int32_t *n_rows_dev;
+    int32_t C;   // 16-byte chunks per row
+};
+
+template <int CPT, bool STREAM_LOAD>
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a)
+{
+    const int r = blockIdx.x;
+    if (a.n_rows_dev && r >= *a.n_rows_dev) return;
+    int q = a.idx1[r];
+    if (q >= 0 && a.idx2) q = a.idx2[q];
+    if (q < 0) return;
+    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    u32x4 v[CPT];
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c < a.C) v[i] = STREAM_LOAD ? load16_stream(a.src + (size_t)q * a.C + c) : a.src[(size_t)q * a.C + c];
+    }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        const int c = c0 + i * blockDim.x;
+        if (c < a.C) a.dst[(size_t)r * a.C + c] = v[i];
+    }
+}
+
+// dev[p] = device of expert A[p] (or -1 for an id outside [0, E)): the key of the rank-major order
+__global__ __launch_bounds__(256) void expert_to_device_kernel(int32_t *dev, const int32_t *A, int64_t n, int E, int Eloc)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    const int e = A[p];
+    dev[p] = (unsigned)e < (unsigned)E ? e / Eloc : -1;
+}
+
+}   // namespace
+
+#endif

@@ -1,0 +1,403 @@
+// Planner kernels: token-expert matrix -> two-level layout descriptor (paper section 3.3).
+#ifndef FUSCO_CSRC_PLANNER_H
+#define FUSCO_CSRC_PLANNER_H
+
+#include "common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Planner
+// ------------------------------------------------------------------------------------------
+struct PlanArgs {
+    const int32_t *A;
+    int32_t N, k, E, D, Eloc;
+    uint32_t k_magic, eloc_magic;   // ceil(2^20 / k), ceil(2^20 / Eloc): see div20
+    int32_t tpt;      // tokens per tile
+    int32_t n_tiles;
+    int32_t stride;   // ints per tile in tile_hist: E expert counts, D device counts, 1 invalid count
+    int32_t *tile_hist;
+    int32_t chunk_tiles, n_chunks;   // 0, 0: no chunk level
+    int32_t *chunk_hist;             // [n_chunks][stride]: tile_hist summed over the tiles of a chunk
+    int32_t *exp_count, *exp_off, *send_count, *send_off;
+    int32_t *pair_slot, *slot_pair, *slot_token, *send_src, *pair_send_row, *slot_send_row;
+    uint8_t *pair_first;
+    int32_t *status;
+};
+
+__device__ __forceinline__ int bits_for(int nb)
+{
+    int n = 0;
+    while ((1 << n) < nb) ++n;
+    return n;
+}
+
+// Lanes of this wave that take part and hold the same key as the calling lane.
+__device__ __forceinline__ uint64_t same_key_lanes(int key, bool part, int nbits)
+{
+    uint64_t m = __builtin_amdgcn_ballot_w64(part);
+    for (int b = 0; b < nbits; ++b) {
+        const bool bit = (key >> b) & 1;
+        const uint64_t bal = __builtin_amdgcn_ballot_w64(bit);
+        m &= bit ? bal : ~bal;
+    }
+    return m;
+}
+
+// n / d for the small operands of the planner (n < 2048 with d <= 64, or n < 1024 with d <= 1024; the
+// callers stay below: pair index in a tile < 1024 over k <= 64, expert id < 1024 over E / D)
+// through magic = ceil(2^20 / d): the error n * (magic * d - 2^20) / (d * 2^20) stays below 1 / d.
+__device__ __forceinline__ int div20(int n, uint32_t magic) { return (int)(((uint32_t)n * magic) >> 20); }
+
+// Orders LDS traffic between the lanes of one wave (no instruction is emitted: LDS serves the
+// accesses of a wave in program order, the fences only stop the compiler from moving them).
+__device__ __forceinline__ void wave_lds_order()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// For the pair at tile-local index p, held by lane `lane` of a round of 64 consecutive pairs:
+// the tile-local index of the first entry of the same token whose expert lives on the same device
+// d (p itself if this pair is that first appearance), or -1 if d < 0.  Must be called by all lanes.
+// `same` receives the lanes of the round with the same device.  tile_dev holds the device of every
+// pair of the tile, row0 is the token's first pair.  Entries of the token inside this round are
+// compared with ballots; only a token that straddles the round's start needs LDS reads.
+__device__ __forceinline__ int first_pair_on_device(const int16_t *tile_dev, int p, int lane, int row0, int d, int dbits,
+                                                    uint64_t &same)
+{
+    same = same_key_lanes(d, d >= 0, dbits);
+    if (d < 0) return -1;
+    const int base = p - lane;
+    for (int q = row0; q < base; ++q)
+        if (tile_dev[q] == d) return q;
+    const int l0 = max(row0 - base, 0);
+    const uint64_t before = same & (((uint64_t)1 << lane) - 1) & ~(((uint64_t)1 << l0) - 1);
+    return before ? base + __builtin_ctzll(before) : p;
+}
+
+// Pass 1 of the multi-tile planner: per-tile counts of pairs per expert and of first
+// (token, device) appearances per device.  Lanes of a wave that hold the same key are found with
+// ballots and only one of them adds their number to the LDS counter, so a popular key does not
+// serialise the wave.  Counts do not depend on the order of the additions.
+__global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
+{
+    __shared__ int16_t tile_dev[kTilePairs];
+    __shared__ int hist[2 * kMaxBins + 1];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int tile = blockIdx.x;
+    const int tok0 = tile * a.tpt;
+    const int ntok = min(a.tpt, a.N - tok0);
+    const int npairs = ntok > 0 ? ntok * a.k : 0;
+    const int64_t pair0 = (int64_t)tok0 * a.k;
+    const int nb = a.E + a.D;
+    const int ebits = bits_for(a.E), dbits = bits_for(a.D);
+    const uint64_t lt = ((uint64_t)1 << lane) - 1;
+
+    for (int b = tid; b <= nb; b += kPlanThreads) hist[b] = 0;
+    int ekey[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = r * kPlanThreads + tid;
+        int key = -1;
+        bool bad = false;
+        if (p < npairs) {
+            const int e = a.A[pair0 + p];
+            if ((unsigned)e < (unsigned)a.E) key = e;
+            else bad = true;
+        }
+        ekey[r] = key;
+        tile_dev[p] = (int16_t)(key >= 0 ? div20(key, a.eloc_magic) : -1);
+        const uint64_t nbad = __builtin_amdgcn_ballot_w64(bad);
+        if (r == 0) __syncthreads();   // counters are zero from here on
+        if (nbad != 0 && lane == 0) atomicAdd(&hist[nb], __builtin_popcountll(nbad));
+        const uint64_t m = same_key_lanes(key, key >= 0, ebits);
+        if (key >= 0 && (m & lt) == 0) atomicAdd(&hist[key], __builtin_popcountll(m));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = r * kPlanThreads + tid;
+        const int d = tile_dev[p];
+        uint64_t same;
+        const bool first = first_pair_on_device(tile_dev, p, lane, div20(p, a.k_magic) * a.k, d, dbits, same) == p;
+        const uint64_t m = same & __builtin_amdgcn_ballot_w64(first);
+        if (first && (m & lt) == 0) atomicAdd(&hist[a.E + d], __builtin_popcountll(m));
+    }
+    __syncthreads();
+    int32_t *out = a.tile_hist + (int64_t)tile * a.stride;
+    for (int b = tid; b <= nb; b += kPlanThreads) out[b] = hist[b];
+}
+
+// Optional pass between counting and placing: sums the per-tile counts over chunks of consecutive
+// tiles.  One workgroup per chunk; the columns are covered 1024 at a time, and where fewer columns
+// than threads remain the tiles of the chunk are split over groups of threads.
+__global__ __launch_bounds__(kPlanThreads) void plan_chunk_kernel(PlanArgs a)
+{
+    __shared__ int acc[kPlanThreads];
+    const int tid = threadIdx.x;
+    const int chunk = blockIdx.x;
+    const int t0 = chunk * a.chunk_tiles, t1 = min(t0 + a.chunk_tiles, a.n_tiles);
+    for (int col0 = 0; col0 < a.stride; col0 += kPlanThreads) {
+        const int ncol = min(a.stride - col0, kPlanThreads);
+        const int pad = (ncol + kWave - 1) / kWave * kWave;
+        const int parts = kPlanThreads / pad;
+        const int part = tid / pad, b = tid - part * pad;
+        acc[tid] = 0;
+        __syncthreads();
+        if (part < parts && b < ncol) {
+            const int32_t *h = a.tile_hist + col0 + b;
+            int sum = 0;
+#pragma unroll 8
+            for (int tl = t0 + part; tl < t1; tl += parts) sum += h[(int64_t)tl * a.stride];
+            atomicAdd(&acc[b], sum);
+        }
+        __syncthreads();
+        if (tid < ncol) a.chunk_hist[(int64_t)chunk * a.stride + col0 + tid] = acc[tid];
+        __syncthreads();
+    }
+}
+
+// Shared LDS state of the placement kernel.
+struct PlaceLds {
+    int16_t tile_dev[kTilePairs];              // device of every pair, -1 for an invalid expert id
+    int tile_row[kTilePairs];                  // send row of the pairs that are first appearances
+    int tile_slot[kTilePairs];                 // expert-major slot of every pair (kept for the fused dispatch)
+    uint16_t wave_cnt[kPlanWaves][kMaxBins];   // per wave and key: running count, then prefix over waves
+    int base[kMaxBins];                        // per key: pairs in earlier tiles, then the tile's global start
+    int total[kMaxBins + 1];
+    int invalid;
+};
+
+// Stable ranking of the tile's participating pairs by key, in pair order, on top of the global
+// order of tiles.  key[r] is the key of pair (wave chunk + r * 64 + lane), or -1 if that pair
+// does not take part.  On return pos[r] is the pair's global position: (global exclusive offset
+// of its key) + (pairs with that key in earlier tiles) + (earlier pairs with that key in this
+// tile).  Block 0 also writes the per-key counts and their exclusive prefix sum.
+template <bool SINGLE>
+__device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int tile, bool writer,
+                                            const int (&key)[kRounds], int nb, int hist_off, int32_t *count_out,
+                                            int32_t *off_out, int (&pos)[kRounds])
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int nbits = bits_for(nb);
+    const uint64_t lt = ((uint64_t)1 << lane) - 1;
+
+    for (int b = lane; b < nb; b += kWave) s.wave_cnt[wave][b] = 0;
+    for (int b = tid; b < nb; b += kPlanThreads) {
+        s.total[b] = 0;
+        s.base[b] = 0;
+    }
+    __syncthreads();
+
+    // rank inside the wave's chunk; wave_cnt[wave][key] is the running count of the key
+    int rank[kRounds];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const bool part = key[r] >= 0;
+        const uint64_t m = same_key_lanes(key[r], part, nbits);
+        const int before = part ? s.wave_cnt[wave][key[r]] : 0;
+        rank[r] = before + __builtin_popcountll(m & lt);
+        wave_lds_order();
+        if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = (uint16_t)(before + __builtin_popcountll(m));
+        wave_lds_order();
+    }
+    __syncthreads();
+
+    // per key: total over all tiles and the part that lies in earlier tiles.  The workgroup splits
+    // the tiles into as many interleaved parts as it has groups of nb threads, so that every
+    // thread keeps only a few independent loads in flight; partial sums meet in LDS.
+    if constexpr (SINGLE) {
+        for (int b = tid; b < nb; b += kPlanThreads) {
+            int tot = 0;
+            for (int w = 0; w < kPlanWaves; ++w) tot += s.wave_cnt[w][b];
+            s.total[b] = tot;
+        }
+    } else {
+        const int nb_pad = (nb + kWave - 1) / kWave * kWave;
+        const int parts = kPlanThreads / nb_pad;     // >= 1 because nb <= kMaxBins == kPlanThreads
+        const int part = tid / nb_pad, b = tid - part * nb_pad;
+        if (part < parts && b < nb) {
+            const int32_t *h = a.tile_hist + hist_off + b;
+            const int me = tile;
+            int tot = 0, pre = 0;
+            if (a.chunk_tiles == 0) {
+#pragma unroll 8
+                for (int tl = part; tl < a.n_tiles; tl += parts) {
+                    const int v = h[(int64_t)tl * a.stride];
+                    tot += v;
+                    pre += tl < me ? v : 0;
+                }
+            } else {
+                // whole chunks from their sums, then the tiles of this workgroup's own chunk before it
+                const int32_t *ch = a.chunk_hist + hist_off + b;
+                const int my_chunk = me / a.chunk_tiles;
+#pragma unroll 8
+                for (int c = part; c < a.n_chunks; c += parts) {
+                    const int v = ch[(int64_t)c * a.stride];
+                    tot += v;
+                    pre += c < my_chunk ? v : 0;
+                }
+#pragma unroll 8
+                for (int tl = my_chunk * a.chunk_tiles + part; tl < me; tl += parts) pre += h[(int64_t)tl * a.stride];
+            }
+            atomicAdd(&s.total[b], tot);
+            atomicAdd(&s.base[b], pre);
+        }
+    }
+    __syncthreads();
+    if (writer && tile == 0)
+        for (int b = tid; b < nb; b += kPlanThreads) count_out[b] = s.total[b];
+
+    // exclusive prefix sum over the keys, by wave 0: each lane owns a run of consecutive keys
+    if (wave == 0) {
+        const int per = (nb + kWave - 1) / kWave;
+        const int lo = min(lane * per, nb), hi = min(lo + per, nb);
+        int sum = 0;
+        for (int b = lo; b < hi; ++b) sum += s.total[b];
+        int incl = sum;
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int up = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += up;
+        }
+        int run = incl - sum;
+        for (int b = lo; b < hi; ++b) {
+            const int v = s.total[b];
+            s.total[b] = run;
+            run += v;
+        }
+        if (lane == kWave - 1) s.total[nb] = incl;
+    }
+    __syncthreads();
+    if (writer && tile == 0)
+        for (int b = tid; b <= nb; b += kPlanThreads) off_out[b] = s.total[b];
+
+    // per key: prefix of the per-wave counts, and the global position where the tile's run starts
+    for (int b = tid; b < nb; b += kPlanThreads) {
+        int run = 0;
+        for (int w = 0; w < kPlanWaves; ++w) {
+            const int c = s.wave_cnt[w][b];
+            s.wave_cnt[w][b] = (uint16_t)run;
+            run += c;
+        }
+        s.base[b] += s.total[b];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+        pos[r] = key[r] >= 0 ? s.base[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
+    __syncthreads();
+}
+
+// Placement of one tile by one workgroup: pass 2 of the multi-tile planner, or the whole plan when the
+// input is a single tile.  A writer stores every descriptor array; a workgroup that is not a writer only
+// keeps the tile's slots in LDS (the fused plan + dispatch kernel runs the single-tile plan redundantly in
+// every workgroup and lets one of them write it out).
+template <bool SINGLE>
+__device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int tile, bool writer)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tok0 = tile * a.tpt;
+    const int ntok = min(a.tpt, a.N - tok0);
+    const int npairs = ntok > 0 ? ntok * a.k : 0;
+    const int64_t pair0 = (int64_t)tok0 * a.k;
+
+    if (tid == 0) s.invalid = 0;
+    __syncthreads();
+    int ekey[kRounds], tl[kRounds];   // expert id and tile-local token of the thread's pairs
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = wave * kWaveChunk + r * kWave + lane;
+        int key = -1;
+        if (p < npairs) {
+            const int e = a.A[pair0 + p];
+            if ((unsigned)e < (unsigned)a.E) key = e;
+            else if constexpr (SINGLE) atomicAdd(&s.invalid, 1);
+        }
+        tl[r] = div20(p, a.k_magic);
+        ekey[r] = key;
+        s.tile_dev[p] = (int16_t)(key >= 0 ? div20(key, a.eloc_magic) : -1);
+    }
+    __syncthreads();
+
+    // level 2 receive side: expert-major slot of every pair
+    int slot[kRounds];
+    rank_by_key<SINGLE>(s, a, tile, writer, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = wave * kWaveChunk + r * kWave + lane;
+        s.tile_slot[p] = slot[r];
+        if (writer && p < npairs) {
+            a.pair_slot[pair0 + p] = slot[r];
+            if (slot[r] >= 0) {
+                a.slot_pair[slot[r]] = (int32_t)(pair0 + p);
+                a.slot_token[slot[r]] = tok0 + tl[r];
+            }
+        }
+    }
+
+    if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
+
+    // level 1: one send row per (token, device), taken at the device's first appearance
+    const int dbits = bits_for(a.D);
+    int dkey[kRounds], jfirst[kRounds];   // jfirst: the token's first pair on the same device
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = wave * kWaveChunk + r * kWave + lane;
+        const int d = s.tile_dev[p];
+        uint64_t same;
+        jfirst[r] = first_pair_on_device(s.tile_dev, p, lane, tl[r] * a.k, d, dbits, same);
+        dkey[r] = jfirst[r] == p ? d : -1;
+    }
+    int row[kRounds];
+    rank_by_key<SINGLE>(s, a, tile, writer, dkey, a.D, a.E, a.send_count, a.send_off, row);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = wave * kWaveChunk + r * kWave + lane;
+        s.tile_row[p] = row[r];
+        if (writer && p < npairs) {
+            a.pair_first[pair0 + p] = row[r] >= 0 ? 1 : 0;
+            if (row[r] >= 0) a.send_src[row[r]] = tok0 + tl[r];
+        }
+    }
+    __syncthreads();
+
+    // level 2 send side: every pair points at the send row of its token on its device
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int p = wave * kWaveChunk + r * kWave + lane;
+        if (!writer || p >= npairs) continue;
+        int srow = -1;
+        if (ekey[r] >= 0) {
+            srow = s.tile_row[jfirst[r]];
+            a.slot_send_row[slot[r]] = srow;
+        }
+        a.pair_send_row[pair0 + p] = srow;
+    }
+
+    if (writer && tile == 0 && wave == 0) {
+        int bad = 0;
+        if constexpr (SINGLE) {
+            bad = s.invalid;
+        } else {
+            // the last column of the counts holds the invalid ids of a tile (or of a chunk of tiles)
+            const int32_t *col = (a.chunk_tiles ? a.chunk_hist : a.tile_hist) + a.E + a.D;
+            const int rows = a.chunk_tiles ? a.n_chunks : a.n_tiles;
+            for (int r = lane; r < rows; r += kWave) bad += col[(int64_t)r * a.stride];
+            for (int d = kWave / 2; d > 0; d >>= 1) bad += __shfl_down(bad, d, kWave);
+        }
+        if (lane == 0) *a.status = bad;
+    }
+}
+
+template <bool SINGLE>
+__global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
+{
+    __shared__ PlaceLds s;
+    place_tile<SINGLE>(s, a, blockIdx.x, true);
+}
+
+}   // namespace
+
+#endif
