@@ -277,6 +277,41 @@ def test_combine_f32_input_matches_oracle(fusco, oracle, N, k, E, D, H, out_dtyp
     _combine_case(fusco, oracle, A, E, D, y, w, out_dtype)
 
 
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_combine_special_values(fusco, oracle, out_dtype):
+    """Zeros of both signs, subnormals, the largest finite values, infinities and NaNs in y, and weights that
+    overflow, underflow and cancel: every finite or infinite result is bit-identical to the oracle's fp32 chain;
+    where the result is a NaN both sides give a NaN (IEEE 754 fixes neither its sign nor its payload)."""
+    rng = np.random.default_rng(99)
+    N, k, E, D, H = 257, 8, 32, 4, 256
+    A = random_topk(rng, N, k, E)
+    special = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x807F, 0x0080, 0x8080, 0x7F7F, 0xFF7F, 0x7F80,
+                        0xFF80, 0x7FC0, 0xFFC1, 0x3F80, 0xBF80, 0x3F81, 0x3F7F, 0x4049, 0x0300], dtype=np.uint16)
+    y = W.bf16_bits(rng.standard_normal((N * k, H)).astype(np.float32))
+    pick = rng.random((N * k, H)) < 0.3
+    y[pick] = special[rng.integers(0, len(special), size=int(pick.sum()))]
+    wv = np.array([0.0, -0.0, 1.0, -1.0, 0.5, 1e-30, -1e-38, 1e30, 3.0e38, 1.0 / 3.0], dtype=np.float32)
+    w = wv[rng.integers(0, len(wv), size=(N, k))]
+    w[:40] = rng.random((40, k)).astype(np.float32)          # ordinary weights on special rows too
+    L, _ = gpu_plan(fusco, A, E, D)
+    want = oracle.plan(A, E, D)
+    out = torch.zeros((N, H), dtype=out_dtype, device="cuda")
+    fusco.fusco_combine(L, bf16_dev(y), dev(w), out)
+    torch.cuda.synchronize()
+    o32, o16 = oracle.combine_f32(y, w, want.pair_slot)
+    nan = np.isnan(o32)
+    assert nan.any() and np.isinf(o32).any() and (np.abs(o32[~nan]) < 1e-38).any()     # the cases are there
+    if out_dtype == torch.float32:
+        got = out.cpu().numpy()
+        assert np.array_equal(np.isnan(got), nan)
+        assert np.array_equal(got.view(np.uint32)[~nan], o32.view(np.uint32)[~nan])
+    else:
+        got = bits_host(out)
+        got_nan = (got & 0x7FFF) > 0x7F80
+        assert np.array_equal(got_nan, nan)
+        assert np.array_equal(got[~nan], o16[~nan])
+
+
 @pytest.mark.parametrize("k", [1, 2, 4, 8])
 def test_dispatch_identity_combine_returns_input_exactly(fusco, k):
     # w = 1/k is dyadic: dispatch -> identity experts -> combine reproduces x bit for bit
