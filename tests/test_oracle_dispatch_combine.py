@@ -172,6 +172,58 @@ def test_bf16_rounding_ties_to_even(oracle):
     assert o16.tolist() == [[0x3F80, 0x3F82, 0x3F81, 0xBF80]]
 
 
+def test_bf16_rounding_is_nearest_representable_over_the_range(oracle):
+    """Definition, not bit tricks: the result is the bfloat16 value nearest to the float (both neighbours are
+    built by truncation and compared in float64), ties go to the even mantissa, values past the largest finite
+    bfloat16 by half a step or more become infinity."""
+    rng = np.random.default_rng(8)
+    bits = rng.integers(0, 1 << 32, size=20000, dtype=np.uint64).astype(np.uint32)
+    # (-0.0 is left out: the chain starts from +0 and w * (-0) + (+0) is +0)
+    edge = np.array([0x00000000, 0x00000001, 0x00007FFF, 0x00008000, 0x00008001, 0x00018000, 0x007F8000,
+                     0x7F7F7FFF, 0x7F7F8000, 0x7F7FFFFF, 0xFF7F8000, 0x7F800000, 0xFF800000, 0x3F808000, 0x3F818000],
+                    dtype=np.uint32)
+    bits = np.concatenate([bits, edge])
+    f = bits.view(np.float32)
+    keep = ~np.isnan(f)
+    bits, f = bits[keep], f[keep]
+    w = np.ones((1, 1), dtype=np.float32)
+    _, o16 = oracle.combine_f32(f.reshape(1, -1), w, np.zeros(1, dtype=np.int32))
+    got = o16.reshape(-1)
+    lo = (bits & 0xFFFF0000).astype(np.uint32)                       # neighbour towards zero
+    hi = lo + np.uint32(0x10000)                                     # next bfloat16 away from zero (may be inf)
+    x = f.astype(np.float64)
+    flo = lo.view(np.float32).astype(np.float64)
+    with np.errstate(all="ignore"):
+        fhi = hi.view(np.float32).astype(np.float64)
+        # an infinite upper neighbour stands for the next power of two in the distance test
+        fhi = np.where(np.isinf(fhi), np.sign(fhi) * 2.0 ** 128, fhi)
+        dlo, dhi = np.abs(x - flo), np.abs(fhi - x)
+    even_lo = ((lo >> 16) & 1) == 0
+    want = np.where(np.isinf(f), lo, np.where((dlo < dhi) | ((dlo == dhi) & even_lo), lo, hi)) >> 16
+    assert np.array_equal(got, want.astype(np.uint16))
+
+
+def test_combine_special_values_follow_ieee(oracle):
+    inf, nan = np.float32(np.inf), np.float32(np.nan)
+    y = np.array([[1.0, -0.0, inf, 1e-45, 3.0e38, nan, 0.0]], dtype=np.float32)
+    one = np.ones((1, 1), dtype=np.float32)
+    z = np.zeros(1, dtype=np.int32)
+    f32, _ = oracle.combine_f32(y, one, z)
+    keep = [0, 2, 3, 4]
+    assert np.array_equal(f32.view(np.uint32)[0, keep], y.view(np.uint32)[0, keep]) and np.isnan(f32[0, 5])
+    # the chain starts from +0: 1 * (-0) + (+0) is +0, as IEEE addition of opposite zeros says
+    assert f32.view(np.uint32)[0, 1] == 0
+    f32, b16 = oracle.combine_f32(y, np.full((1, 1), 2.0, dtype=np.float32), z)
+    assert f32[0, 4] == inf and b16[0, 4] == 0x7F80            # overflow in the product
+    assert f32[0, 3] == np.float32(2.8e-45)                    # a subnormal stays a subnormal (no flush to zero)
+    f32, _ = oracle.combine_f32(y, np.zeros((1, 1), dtype=np.float32), z)
+    assert np.isnan(f32[0, 2]) and f32[0, 0] == 0.0            # 0 * inf is a NaN
+    # inf - inf over two terms
+    y2 = np.array([[inf], [inf]], dtype=np.float32)
+    f32, b16 = oracle.combine_f32(y2, np.array([[1.0, -1.0]], dtype=np.float32), np.array([0, 1], dtype=np.int32))
+    assert np.isnan(f32[0, 0]) and (b16[0, 0] & 0x7FFF) > 0x7F80
+
+
 # ---- combine along the two levels in reverse (per-device partial sums) ----
 
 def test_two_hop_combine_single_device_equals_flat_sum(oracle):
