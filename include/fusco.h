@@ -94,7 +94,8 @@ const char *fusco_status_string(int status);
  */
 size_t fusco_layout_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
 
-/* Bytes of planner scratch (per-tile partial counts) for these sizes; 0 if the sizes are invalid. */
+/* Bytes of planner scratch (partial counts per tile of 1024 pairs and per chunk of tiles) for these
+ * sizes; 0 if the sizes are invalid. */
 size_t fusco_scratch_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
 
 /*
@@ -108,8 +109,9 @@ int fusco_layout_bind(fusco_layout *L, int32_t N, int32_t k, int32_t E, int32_t 
  * Planner (section 3.3): per-expert histogram, prefix-scan offsets, stable expert-major slot of
  * every (t, e) pair, and removal of duplicate (token, device) sends with the resulting send rows.
  * d_topk_idx: [N, k] int32 row-major, the token-expert matrix A (may be NULL when N == 0).
- * Ids outside [0, E) are counted in L->status, get pair_slot = pair_send_row = -1 and are skipped by dispatch and combine; the
- * plan is then not a valid layout (slots at the end of the tensor stay unassigned).
+ * Ids outside [0, E) are counted in L->status, get pair_slot = pair_send_row = -1 and are skipped
+ * by dispatch and combine; the plan is then not a valid layout (slots at the end of the tensor
+ * stay unassigned).
  * d_scratch: at least fusco_scratch_bytes() bytes, contents irrelevant before and after.
  * Every descriptor array is fully rewritten (send_src only in rows < U).  N == 0 is allowed.
  */
