@@ -321,7 +321,7 @@ def main() -> int:
 
     # decode-sized inputs (one planner tile): the same step with plan and dispatch in one launch
     fused = None
-    if cfg.N <= 1024 // cfg.k and len(sets) == 1 and not args.graph:
+    if cfg.N <= 2048 // cfg.k and len(sets) == 1 and not args.graph:
         def fused_step():
             fusco.fusco_plan_dispatch(L, d_A, d_x, d_expert, **{k_: v for k_, v in dispatch_kwargs.items()})
             fusco.fusco_combine(L, d_y, d_w, d_out)

@@ -94,8 +94,8 @@ const char *fusco_status_string(int status);
  */
 size_t fusco_layout_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
 
-/* Bytes of planner scratch (partial counts per tile of 1024 pairs and per chunk of tiles) for these
- * sizes; 0 if the sizes are invalid. */
+/* Bytes of planner scratch (partial counts per tile of 1024 or 2048 pairs and per chunk of tiles) for
+ * these sizes; 0 if the sizes are invalid. */
 size_t fusco_scratch_bytes(int32_t N, int32_t k, int32_t E, int32_t D);
 
 /*
@@ -141,7 +141,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
 
 /*
  * fusco_plan followed by fusco_dispatch (FUSCO_DISPATCH_EXPERT only) in a single launch, for inputs
- * that fit one planner tile: N <= floor(1024 / k) tokens (decode-sized batches, where a chain of
+ * that fit one planner tile: N <= floor(2048 / k) tokens (decode-sized batches, where a chain of
  * dependent launches costs more than the work; the planner's cost is fixed and shows at small
  * sizes, section 5.2).  Results are exactly those of the two calls: every descriptor array of *L is
  * written as by fusco_plan (no scratch is needed), d_expert_buf / d_expert_aux as by fusco_dispatch.

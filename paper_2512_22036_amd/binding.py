@@ -216,7 +216,7 @@ def fusco_plan_dispatch(layout: Layout, topk_idx: torch.Tensor, x: torch.Tensor,
                         x_aux: Optional[torch.Tensor] = None, expert_aux: Optional[torch.Tensor] = None,
                         stream=None) -> None:
     """fusco_plan and fusco_dispatch (expert tensor only) in one launch; inputs of one planner tile only
-    (N * k <= 1024 with whole tokens), FuscoError otherwise."""
+    (N <= 2048 // k), FuscoError otherwise."""
     if (not topk_idx.is_cuda or topk_idx.dtype != torch.int32 or not topk_idx.is_contiguous()
             or tuple(topk_idx.shape) != (layout.N, layout.k)):
         raise FuscoError("topk_idx must be a contiguous int32 device tensor of shape [N, k]")

@@ -16,13 +16,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWave = 64;
 constexpr int kPlanThreads = 1024;                      // 16 waves per planner workgroup
 constexpr int kPlanWaves = kPlanThreads / kWave;
-constexpr int kTilePairs = 1024;                        // (token, expert) pairs per planner tile
-constexpr int kRounds = kTilePairs / kPlanThreads;      // 64-pair rounds per wave
-constexpr int kWaveChunk = kTilePairs / kPlanWaves;     // consecutive pairs owned by one wave
+// A planner tile holds R * 1024 (token, expert) pairs, R rounds of 64 pairs per wave.  One round is fastest
+// for the sizes a GPU usually plans at once; two rounds halve the number of tiles of very large inputs and
+// let the single-launch paths take inputs of up to 2048 pairs.  (Four would not fit 64 KiB of LDS.)
+constexpr int kMaxRounds = 2;
+constexpr int kRoundPairs = kPlanThreads;               // pairs of one round of the whole workgroup
 constexpr int kMaxBins = FUSCO_MAX_E;
 constexpr size_t kMaxRowChunks = FUSCO_MAX_ROW_BYTES / 16;
 
-static_assert(kTilePairs >= FUSCO_MAX_K, "a tile must hold at least one token");
+static_assert(kRoundPairs >= FUSCO_MAX_K, "a tile must hold at least one token");
 static_assert(kMaxBins <= kPlanThreads, "the planner gives every bin a thread");
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -37,27 +39,45 @@ bool sizes_ok(int32_t N, int32_t k, int32_t E, int32_t D)
 
 // From this many tiles on, per-tile counts are first summed over chunks of tiles (one more small launch),
 // so that a placement workgroup reads about 2 * sqrt(tiles) rows of counts instead of one per tile.
-constexpr int kChunkMinTiles = 320;
+// Measured: with one round per tile the extra launch pays from about 320 tiles, with two rounds from 96.
+inline int chunk_min_tiles(int rounds) { return rounds == 1 ? 320 : 96; }
 
-inline int tokens_per_tile(int k) { return kTilePairs / k; }
-inline int num_tiles(int N, int k)
+inline int tokens_per_tile(int k, int rounds) { return rounds * kRoundPairs / k; }
+inline int num_tiles(int N, int k, int rounds)
 {
-    const int tpt = tokens_per_tile(k);
+    const int tpt = tokens_per_tile(k, rounds);
     const int n = (N + tpt - 1) / tpt;
     return n < 1 ? 1 : n;
 }
 
-// tiles per chunk (a power of two near sqrt(n_tiles)), or 0 when the tiles are few enough to be read one by one
-inline int chunk_tiles_for(int n_tiles)
+// Rounds with which the whole input is one tile (single-launch planner, fused plan + dispatch), or 0.
+inline int single_tile_rounds(int N, int k)
 {
-    if (n_tiles < kChunkMinTiles) return 0;
+    for (int r = 1; r <= kMaxRounds; r *= 2)
+        if (N <= tokens_per_tile(k, r)) return r;
+    return 0;
+}
+
+// Rounds per tile of the planner for these sizes: measured on MI355X, one round wins up to a few hundred
+// thousand pairs, two rounds above.
+inline int plan_rounds(int N, int k)
+{
+    const int single = single_tile_rounds(N, k);
+    if (single) return single;
+    return (int64_t)N * k <= 393216 ? 1 : 2;
+}
+
+// tiles per chunk (a power of two near sqrt(n_tiles)), or 0 when the tiles are few enough to be read one by one
+inline int chunk_tiles_for(int n_tiles, int rounds)
+{
+    if (n_tiles < chunk_min_tiles(rounds)) return 0;
     int c = 8;
     while (c * c < n_tiles) c *= 2;
     return c;
 }
-inline int num_chunks(int n_tiles)
+inline int num_chunks(int n_tiles, int rounds)
 {
-    const int c = chunk_tiles_for(n_tiles);
+    const int c = chunk_tiles_for(n_tiles, rounds);
     return c ? (n_tiles + c - 1) / c : 0;
 }
 

@@ -70,8 +70,9 @@ size_t fusco_layout_bytes(int32_t N, int32_t k, int32_t E, int32_t D)
 size_t fusco_scratch_bytes(int32_t N, int32_t k, int32_t E, int32_t D)
 {
     if (!sizes_ok(N, k, E, D)) return 0;
-    const int tiles = num_tiles(N, k);
-    return align_up(((size_t)tiles + (size_t)num_chunks(tiles)) * (size_t)(E + D + 1) * 4, 256);
+    const int rounds = plan_rounds(N, k);
+    const int tiles = num_tiles(N, k, rounds);
+    return align_up(((size_t)tiles + (size_t)num_chunks(tiles, rounds)) * (size_t)(E + D + 1) * 4, 256);
 }
 
 int fusco_layout_bind(fusco_layout *L, int32_t N, int32_t k, int32_t E, int32_t D, void *d_mem, size_t bytes)
@@ -91,19 +92,19 @@ static bool layout_ok(const fusco_layout *L)
            L->slot_token && L->send_src && L->pair_send_row && L->slot_send_row && L->pair_first && L->status;
 }
 
-static PlanArgs plan_args(const fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch)
+static PlanArgs plan_args(const fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, int rounds)
 {
     PlanArgs a;
     a.A = d_topk_idx;
     a.N = L->N; a.k = L->k; a.E = L->E; a.D = L->D; a.Eloc = L->E / L->D;
     a.k_magic = ((1u << 20) + a.k - 1) / a.k;
     a.eloc_magic = ((1u << 20) + a.Eloc - 1) / a.Eloc;
-    a.tpt = tokens_per_tile(L->k);
-    a.n_tiles = num_tiles(L->N, L->k);
+    a.tpt = tokens_per_tile(L->k, rounds);
+    a.n_tiles = num_tiles(L->N, L->k, rounds);
     a.stride = L->E + L->D + 1;
     a.tile_hist = (int32_t *)d_scratch;   // unused (may be NULL) when the input is a single tile
-    a.chunk_tiles = chunk_tiles_for(a.n_tiles);
-    a.n_chunks = num_chunks(a.n_tiles);
+    a.chunk_tiles = chunk_tiles_for(a.n_tiles, rounds);
+    a.n_chunks = num_chunks(a.n_tiles, rounds);
     a.chunk_hist = a.tile_hist + (size_t)a.n_tiles * (size_t)a.stride;
     a.exp_count = L->exp_count; a.exp_off = L->exp_off; a.send_count = L->send_count; a.send_off = L->send_off;
     a.pair_slot = L->pair_slot; a.slot_pair = L->slot_pair; a.slot_token = L->slot_token; a.send_src = L->send_src;
@@ -116,15 +117,20 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
 {
     if (!layout_ok(L) || (!d_topk_idx && L->N > 0) || !d_scratch) return FUSCO_ERR_INVALID_ARG;
     if (scratch_bytes < fusco_scratch_bytes(L->N, L->k, L->E, L->D)) return FUSCO_ERR_WORKSPACE;
-    const PlanArgs a = plan_args(L, d_topk_idx, d_scratch);
+    const int rounds = plan_rounds(L->N, L->k);
+    const PlanArgs a = plan_args(L, d_topk_idx, d_scratch, rounds);
     hipStream_t s = (hipStream_t)stream;
     const ArmedEvents ev;
+    const dim3 block(kPlanThreads), tiles((unsigned)a.n_tiles);
     if (a.n_tiles == 1) {
-        launch(plan_place_kernel<true>, dim3(1), dim3(kPlanThreads), s, a, ev.start, ev.stop);
+        if (rounds == 1) launch(plan_place_kernel<true, 1>, dim3(1), block, s, a, ev.start, ev.stop);
+        else launch(plan_place_kernel<true, 2>, dim3(1), block, s, a, ev.start, ev.stop);
     } else {
-        launch(plan_count_kernel, dim3(a.n_tiles), dim3(kPlanThreads), s, a, ev.start, nullptr);
-        if (a.n_chunks > 0) launch(plan_chunk_kernel, dim3(a.n_chunks), dim3(kPlanThreads), s, a);
-        launch(plan_place_kernel<false>, dim3(a.n_tiles), dim3(kPlanThreads), s, a, nullptr, ev.stop);
+        if (rounds == 1) launch(plan_count_kernel<1>, tiles, block, s, a, ev.start, nullptr);
+        else launch(plan_count_kernel<2>, tiles, block, s, a, ev.start, nullptr);
+        if (a.n_chunks > 0) launch(plan_chunk_kernel, dim3((unsigned)a.n_chunks), block, s, a);
+        if (rounds == 1) launch(plan_place_kernel<false, 1>, tiles, block, s, a, nullptr, ev.stop);
+        else launch(plan_place_kernel<false, 2>, tiles, block, s, a, nullptr, ev.stop);
     }
     return launch_status();
 }
@@ -136,13 +142,14 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     if (!layout_ok(L) || (!d_topk_idx && L->N > 0)) return FUSCO_ERR_INVALID_ARG;
     if (row_bytes == 0 || row_bytes % 16 != 0 || aux_row_bytes % 16 != 0) return FUSCO_ERR_INVALID_ARG;
     if ((row_bytes + aux_row_bytes) / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
-    if (num_tiles(L->N, L->k) != 1) return FUSCO_ERR_UNSUPPORTED;
+    const int rounds = single_tile_rounds(L->N, L->k);
+    if (rounds == 0) return FUSCO_ERR_UNSUPPORTED;
     if (L->N > 0) {
         if (!d_x || !d_expert_buf || (aux_row_bytes && (!d_x_aux || !d_expert_aux))) return FUSCO_ERR_INVALID_ARG;
         if (!aligned16(d_x) || !aligned16(d_x_aux) || !aligned16(d_expert_buf) || !aligned16(d_expert_aux))
             return FUSCO_ERR_INVALID_ARG;
     }
-    const PlanArgs a = plan_args(L, d_topk_idx, nullptr);
+    const PlanArgs a = plan_args(L, d_topk_idx, nullptr, rounds);
     DispatchArgs m;
     m.x = (const u32x4 *)d_x; m.x_aux = (const u32x4 *)d_x_aux;
     m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
@@ -153,10 +160,14 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     m.write_expert = 1; m.write_wire = 0;
     const ArmedEvents ev;
     const dim3 grid((unsigned)(L->N > 0 ? L->N : 1)), block(kPlanThreads);
-    if (ev.start || ev.stop)
-        hipExtLaunchKernelGGL(plan_dispatch_kernel, grid, block, 0, (hipStream_t)stream, ev.start, ev.stop, 0, a, m);
-    else
-        hipLaunchKernelGGL(plan_dispatch_kernel, grid, block, 0, (hipStream_t)stream, a, m);
+    hipStream_t s = (hipStream_t)stream;
+    if (ev.start || ev.stop) {
+        if (rounds == 1) hipExtLaunchKernelGGL(plan_dispatch_kernel<1>, grid, block, 0, s, ev.start, ev.stop, 0, a, m);
+        else hipExtLaunchKernelGGL(plan_dispatch_kernel<2>, grid, block, 0, s, ev.start, ev.stop, 0, a, m);
+    } else {
+        if (rounds == 1) hipLaunchKernelGGL(plan_dispatch_kernel<1>, grid, block, 0, s, a, m);
+        else hipLaunchKernelGGL(plan_dispatch_kernel<2>, grid, block, 0, s, a, m);
+    }
     return launch_status();
 }
 

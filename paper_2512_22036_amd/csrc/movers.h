@@ -91,9 +91,10 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 // requested before the planning starts, so that its latency hides behind it.
 constexpr int kFusedPreload = 4;   // 16-byte chunks per thread held in registers across the planning
 
+template <int R>
 __global__ __launch_bounds__(kPlanThreads) void plan_dispatch_kernel(PlanArgs a, DispatchArgs m)
 {
-    __shared__ PlaceLds s;
+    __shared__ PlaceLds<R> s;
     const int tid = threadIdx.x;
     const int t = blockIdx.x;   // the grid has max(N, 1) workgroups
     const int Ct = m.C + m.Ca;
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_dispatch_kernel(PlanArgs a,
             else if (c < Ct) v[i] = load16_stream(m.x_aux + (size_t)t * m.Ca + (c - m.C));
         }
     }
-    place_tile<true>(s, a, 0, blockIdx.x == 0);
+    place_tile<true, R>(s, a, 0, blockIdx.x == 0);
     __syncthreads();
     if (t >= a.N) return;
     const int *slots = s.tile_slot + t * a.k;

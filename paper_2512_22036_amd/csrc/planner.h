@@ -81,9 +81,10 @@ __device__ __forceinline__ int first_pair_on_device(const int16_t *tile_dev, int
 // (token, device) appearances per device.  Lanes of a wave that hold the same key are found with
 // ballots and only one of them adds their number to the LDS counter, so a popular key does not
 // serialise the wave.  Counts do not depend on the order of the additions.
+template <int R>
 __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
 {
-    __shared__ int16_t tile_dev[kTilePairs];
+    __shared__ int16_t tile_dev[R * kRoundPairs];
     __shared__ int hist[2 * kMaxBins + 1];
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int tile = blockIdx.x;
@@ -96,9 +97,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
     const uint64_t lt = ((uint64_t)1 << lane) - 1;
 
     for (int b = tid; b <= nb; b += kPlanThreads) hist[b] = 0;
-    int ekey[kRounds];
+    int ekey[R];
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const int p = r * kPlanThreads + tid;
         int key = -1;
         bool bad = false;
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanArgs a)
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const int p = r * kPlanThreads + tid;
         const int d = tile_dev[p];
         uint64_t same;
@@ -160,10 +161,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_chunk_kernel(PlanArgs a)
 }
 
 // Shared LDS state of the placement kernel.
+template <int R>
 struct PlaceLds {
-    int16_t tile_dev[kTilePairs];              // device of every pair, -1 for an invalid expert id
-    int tile_row[kTilePairs];                  // send row of the pairs that are first appearances
-    int tile_slot[kTilePairs];                 // expert-major slot of every pair (kept for the fused dispatch)
+    int16_t tile_dev[R * kRoundPairs];              // device of every pair, -1 for an invalid expert id
+    int tile_row[R * kRoundPairs];                  // send row of the pairs that are first appearances
+    int tile_slot[R * kRoundPairs];                 // expert-major slot of every pair (kept for the fused dispatch)
     uint16_t wave_cnt[kPlanWaves][kMaxBins];   // per wave and key: running count, then prefix over waves
     int base[kMaxBins];                        // per key: pairs in earlier tiles, then the tile's global start
     int total[kMaxBins + 1];
@@ -175,10 +177,10 @@ struct PlaceLds {
 // does not take part.  On return pos[r] is the pair's global position: (global exclusive offset
 // of its key) + (pairs with that key in earlier tiles) + (earlier pairs with that key in this
 // tile).  Block 0 also writes the per-key counts and their exclusive prefix sum.
-template <bool SINGLE>
-__device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int tile, bool writer,
-                                            const int (&key)[kRounds], int nb, int hist_off, int32_t *count_out,
-                                            int32_t *off_out, int (&pos)[kRounds])
+template <bool SINGLE, int R>
+__device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, int tile, bool writer,
+                                            const int (&key)[R], int nb, int hist_off, int32_t *count_out,
+                                            int32_t *off_out, int (&pos)[R])
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int nbits = bits_for(nb);
@@ -192,9 +194,9 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int 
     __syncthreads();
 
     // rank inside the wave's chunk; wave_cnt[wave][key] is the running count of the key
-    int rank[kRounds];
+    int rank[R];
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
+    for (int r = 0; r < R; ++r) {
         const bool part = key[r] >= 0;
         const uint64_t m = same_key_lanes(key[r], part, nbits);
         const int before = part ? s.wave_cnt[wave][key[r]] : 0;
@@ -285,7 +287,7 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int 
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
+    for (int r = 0; r < R; ++r)
         pos[r] = key[r] >= 0 ? s.base[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
     __syncthreads();
 }
@@ -294,8 +296,8 @@ __device__ __forceinline__ void rank_by_key(PlaceLds &s, const PlanArgs &a, int 
 // input is a single tile.  A writer stores every descriptor array; a workgroup that is not a writer only
 // keeps the tile's slots in LDS (the fused plan + dispatch kernel runs the single-tile plan redundantly in
 // every workgroup and lets one of them write it out).
-template <bool SINGLE>
-__device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int tile, bool writer)
+template <bool SINGLE, int R>
+__device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, int tile, bool writer)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int tok0 = tile * a.tpt;
@@ -305,10 +307,10 @@ __device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int t
 
     if (tid == 0) s.invalid = 0;
     __syncthreads();
-    int ekey[kRounds], tl[kRounds];   // expert id and tile-local token of the thread's pairs
+    int ekey[R], tl[R];   // expert id and tile-local token of the thread's pairs
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int p = wave * kWaveChunk + r * kWave + lane;
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
         int key = -1;
         if (p < npairs) {
             const int e = a.A[pair0 + p];
@@ -322,11 +324,11 @@ __device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int t
     __syncthreads();
 
     // level 2 receive side: expert-major slot of every pair
-    int slot[kRounds];
-    rank_by_key<SINGLE>(s, a, tile, writer, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
+    int slot[R];
+    rank_by_key<SINGLE, R>(s, a, tile, writer, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int p = wave * kWaveChunk + r * kWave + lane;
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
         s.tile_slot[p] = slot[r];
         if (writer && p < npairs) {
             a.pair_slot[pair0 + p] = slot[r];
@@ -341,20 +343,20 @@ __device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int t
 
     // level 1: one send row per (token, device), taken at the device's first appearance
     const int dbits = bits_for(a.D);
-    int dkey[kRounds], jfirst[kRounds];   // jfirst: the token's first pair on the same device
+    int dkey[R], jfirst[R];   // jfirst: the token's first pair on the same device
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int p = wave * kWaveChunk + r * kWave + lane;
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
         const int d = s.tile_dev[p];
         uint64_t same;
         jfirst[r] = first_pair_on_device(s.tile_dev, p, lane, tl[r] * a.k, d, dbits, same);
         dkey[r] = jfirst[r] == p ? d : -1;
     }
-    int row[kRounds];
-    rank_by_key<SINGLE>(s, a, tile, writer, dkey, a.D, a.E, a.send_count, a.send_off, row);
+    int row[R];
+    rank_by_key<SINGLE, R>(s, a, tile, writer, dkey, a.D, a.E, a.send_count, a.send_off, row);
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int p = wave * kWaveChunk + r * kWave + lane;
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
         s.tile_row[p] = row[r];
         if (writer && p < npairs) {
             a.pair_first[pair0 + p] = row[r] >= 0 ? 1 : 0;
@@ -365,8 +367,8 @@ __device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int t
 
     // level 2 send side: every pair points at the send row of its token on its device
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int p = wave * kWaveChunk + r * kWave + lane;
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
         if (!writer || p >= npairs) continue;
         int srow = -1;
         if (ekey[r] >= 0) {
@@ -391,11 +393,11 @@ __device__ __forceinline__ void place_tile(PlaceLds &s, const PlanArgs &a, int t
     }
 }
 
-template <bool SINGLE>
+template <bool SINGLE, int R>
 __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
 {
-    __shared__ PlaceLds s;
-    place_tile<SINGLE>(s, a, blockIdx.x, true);
+    __shared__ PlaceLds<R> s;
+    place_tile<SINGLE, R>(s, a, blockIdx.x, true);
 }
 
 }   // namespace

@@ -114,8 +114,8 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert pd(buf, buf, 64, None, 16, buf, None, None) == -1                     # aux plane without tensors
     assert pd(buf, buf + 8, 64, None, 0, buf, None, None) == -1                  # misaligned
     Lbig = _CLayout()
-    assert lib.fusco_layout_bind(ctypes.byref(Lbig), 1025, 1, E, D, base + (1 << 26), lib.fusco_layout_bytes(1025, 1, E, D)) == 0
-    assert lib.fusco_plan_dispatch(ctypes.byref(Lbig), buf, buf, 64, None, 0, buf, None, None) == -3   # two tiles
+    assert lib.fusco_layout_bind(ctypes.byref(Lbig), 2049, 1, E, D, base + (1 << 26), lib.fusco_layout_bytes(2049, 1, E, D)) == 0
+    assert lib.fusco_plan_dispatch(ctypes.byref(Lbig), buf, buf, 64, None, 0, buf, None, None) == -3   # more than one tile
     # an empty layout takes NULL tensors (nothing is launched), sizes are still checked
     L0 = _CLayout()
     assert lib.fusco_layout_bind(ctypes.byref(L0), 0, k, E, D, base + (1 << 25), lib.fusco_layout_bytes(0, k, E, D)) == 0

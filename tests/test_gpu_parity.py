@@ -54,11 +54,13 @@ def assert_plan_equal(got, want):
 
 
 PLAN_SHAPES = [
-    # N, k, E, D, distinct experts per token       (a planner tile holds 1024 pairs)
+    # N, k, E, D, distinct experts per token
+    # (a planner tile holds 1024 pairs, or 2048 for single-tile inputs and above 393216 pairs)
     (1, 1, 1, 1, True), (1, 8, 256, 8, True), (5, 2, 4, 2, True), (64, 2, 16, 4, True),
-    (128, 8, 256, 8, True),        # exactly one tile
-    (129, 8, 256, 8, True),        # one tile and one token
-    (256, 8, 256, 8, True), (257, 8, 256, 8, True),
+    (128, 8, 256, 8, True),        # exactly one tile of 1024 pairs
+    (129, 8, 256, 8, True),        # one tile of 2048 pairs
+    (256, 8, 256, 8, True),        # exactly one tile of 2048 pairs
+    (257, 8, 256, 8, True),        # three tiles of 1024 pairs, the last holding one token
     (1000, 8, 256, 8, True),       # several tiles, ragged tail
     (4096, 2, 16, 4, True), (3000, 8, 128, 16, True), (777, 6, 96, 12, True),
     (300, 64, 1024, 64, True),     # largest k and E
@@ -66,13 +68,15 @@ PLAN_SHAPES = [
     (900, 4, 64, 1, True),         # single device
     (1300, 5, 10, 5, False),       # repeated experts inside a token
     (2100, 7, 7, 7, False), (129, 33, 66, 2, True),
-    # many tiles: from 320 tiles on, per-tile counts are first summed over chunks of tiles
+    # many tiles: per-tile counts are first summed over chunks of tiles (from 320 tiles of 1024 pairs on)
     (40832, 8, 256, 8, False),     # 319 tiles: the last size read tile by tile
     (40833, 8, 256, 8, False),     # 320 tiles, the last one holding one token
     (30011, 8, 64, 16, True),      # 235 tiles, ragged
-    (50011, 8, 64, 16, True),      # 391 tiles in chunks of 32, ragged
     (5200, 64, 1024, 1024, True),  # 325 tiles, more count columns than threads
-    (600000, 8, 32, 4, False),     # 4688 tiles, chunks of 128, last chunk ragged
+    (49152, 8, 256, 8, False),     # 393216 pairs: the last size planned in tiles of 1024 pairs (384 tiles)
+    (49153, 8, 256, 8, False),     # tiles of 2048 pairs from here on: 193 tiles in chunks of 16
+    (50011, 8, 64, 16, True),      # 196 tiles of 2048 pairs, ragged
+    (600000, 8, 32, 4, False),     # 2344 tiles of 2048 pairs, chunks of 64, last chunk ragged
 ]
 
 
@@ -136,7 +140,7 @@ def test_plan_is_deterministic(fusco):
         assert torch.equal(L.mem, ref)
 
 
-@pytest.mark.parametrize("N", [700, 90000])          # one-level and chunked counts (352 tiles)
+@pytest.mark.parametrize("N", [700, 90000, 150000])          # one-level and chunked counts (352 tiles of 1024 pairs)
 def test_plan_counts_invalid_ids(fusco, oracle, N):
     rng = np.random.default_rng(77)
     k, E, D = 4, 32, 4
@@ -372,12 +376,15 @@ def test_decode_fp8_config(fusco, oracle):
 
 
 FUSED_SHAPES = [
-    # N, k, E, D, row_bytes, aux_row_bytes, distinct       (one planner tile: N <= 1024 // k)
+    # N, k, E, D, row_bytes, aux_row_bytes, distinct       (one planner tile: N <= 2048 // k)
     (1, 1, 1, 1, 16, 0, True), (128, 8, 256, 64, 7168, 224, True), (128, 8, 256, 8, 14336, 0, True),
     (1024, 1, 8, 4, 48, 16, True), (16, 64, 1024, 64, 4096, 0, True), (31, 33, 66, 2, 16 * 129, 0, True),
     (100, 5, 10, 5, 16 * 37, 0, False),                       # repeated experts inside a token
     (3, 2, 4, 2, 16 * 5000, 16 * 9, True),                    # row longer than the part held in registers
     (2, 2, 4, 2, 1 << 20, 0, True),                           # the largest row
+    # tiles of 2048 pairs
+    (129, 8, 256, 8, 2048, 0, True), (256, 8, 256, 64, 7168, 224, True), (2048, 1, 16, 4, 32, 0, True),
+    (32, 64, 1024, 64, 1024, 16, True), (62, 33, 66, 2, 16 * 7, 0, True), (400, 5, 10, 5, 64, 0, False),
 ]
 
 
@@ -431,12 +438,12 @@ def test_fused_plan_dispatch_edge_cases(fusco, oracle):
     torch.cuda.synchronize()
     assert int(L1.array("status").item()) == 3
     assert torch.equal(L1.mem, L2.mem) and torch.equal(e1, e2)
-    # more than one tile: refused, nothing launched
-    Lb = fusco.Layout(129, 8, 256, 8)
+    # more than 2048 pairs: refused, nothing launched
+    Lb = fusco.Layout(257, 8, 256, 8)
     with pytest.raises(fusco.FuscoError):
-        fusco.fusco_plan_dispatch(Lb, torch.zeros((129, 8), dtype=torch.int32, device="cuda"),
-                                  torch.zeros((129, 64), dtype=torch.uint8, device="cuda"),
-                                  torch.zeros((129 * 8, 64), dtype=torch.uint8, device="cuda"))
+        fusco.fusco_plan_dispatch(Lb, torch.zeros((257, 8), dtype=torch.int32, device="cuda"),
+                                  torch.zeros((257, 64), dtype=torch.uint8, device="cuda"),
+                                  torch.zeros((257 * 8, 64), dtype=torch.uint8, device="cuda"))
 
 
 def test_binding_rejects_wrong_shapes(fusco):
