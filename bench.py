@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # profiles/bench_dsv3_hbm_traffic_pmc.txt: FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by what
 # the same counter reads for the 1 GiB plain-copy probe (1.99994 and 1.00000 KiB per count).
 MEASURED_TRAFFIC_BYTES = {
-    "dsv3": {"dispatch": 119480125 + 939524096, "combine": 941656208 + 117440512},
+    "dsv3": {"dispatch": 119459533 + 939524096, "combine": 941655877 + 117440512},
 }
 
 
