@@ -33,6 +33,19 @@ def test_header_functions_are_exported(lib):
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c_and_cxx():
+    """The boundary is a C header: it must compile on its own as C99 and as C++ (no HIP or torch types)."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "fusco.h")
+    if not shutil.which("gcc") or not shutil.which("g++"):
+        pytest.skip("no host compiler")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header])
+    text = open(header).read()
+    assert "hip/" not in text and "torch" not in text.lower()
+
+
 def test_version_and_status_strings(lib):
     assert lib.fusco_version() == 100
     assert lib.fusco_status_string(0) == b"ok"
