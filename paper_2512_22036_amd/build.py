@@ -36,5 +36,24 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(ROOT, "examples", "c_abi_usage.c")
+EXAMPLE_BIN = os.path.join(ROOT, "examples", "c_abi_usage")
+
+
+def build_c_example(verbose: bool = False) -> str:
+    """Compile the plain-C user of the boundary (host compiler only) against the built library."""
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(hipcc_path())))
+    if not os.path.isdir(os.path.join(rocm, "include", "hip")):
+        rocm = "/opt/rocm"
+    cmd = ["gcc", "-std=c99", "-Wall", "-O1", EXAMPLE_SRC, "-I", INCLUDE, "-I", os.path.join(rocm, "include"),
+           "-D__HIP_PLATFORM_AMD__", "-L", HERE, "-lfusco", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2512_22036_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_example(verbose=True))

@@ -237,3 +237,14 @@ def test_calls_follow_the_given_stream_and_can_be_captured_in_a_graph(fusco, ora
         assert np.array_equal(bits_host(out), out_want), i
         got = L.to_host()
         assert np.array_equal(got.pair_slot, want.pair_slot) and np.array_equal(got.send_src, want.send_src)
+
+
+def test_plain_c_program_uses_the_boundary_without_python(fusco):
+    """examples/c_abi_usage.c: HIP runtime + the C boundary only; it checks its own results and prints ok."""
+    import os
+    import subprocess
+    from paper_2512_22036_amd import build
+    if not os.path.exists(build.EXAMPLE_BIN):
+        build.build_c_example()          # host compiler only, a second or two
+    res = subprocess.run([build.EXAMPLE_BIN], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
+    assert res.returncode == 0 and "c_abi_usage ok" in res.stdout, res.stdout
