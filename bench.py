@@ -96,6 +96,9 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     d_send = torch.empty((L.send_cap, cfg.H), dtype=torch.bfloat16, device="cuda")
     two_hop = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=fusco.DISPATCH_TWO_HOP))
     wire = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, d_expert, send_buf=d_send, flags=3))
+    # level 1 alone, with and without the planner's duplicate removal ("Planner-off"): packing what would go
+    # on the links, one row per (token, device) against one row per (token, expert) in device-major order
+    wire_only = mean_ms(lambda: fusco.fusco_dispatch(L, d_x, None, send_buf=d_send, flags=fusco.DISPATCH_WIRE))
     del d_send
     d_part = torch.empty((L.send_cap, cfg.H), dtype=torch.float32, device="cuda")
     two_hop_c = mean_ms(lambda: fusco.fusco_combine_two_hop(L, d_expert, d_w, d_part, d_out))
@@ -120,6 +123,7 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     Lr = fusco.Layout(cfg.N, cfg.k, cfg.D, cfg.D)
     d_dev = torch.empty_like(d_A)
     rank_plan = mean_ms(lambda: fusco.fusco_disaggregated_plan(Lr, L, d_A, d_dev))
+    wire_no_dedup = mean_ms(lambda: fusco.fusco_dispatch(Lr, d_x, d_expert))     # device-major, one row per pair
     st_a = torch.empty_like(d_expert)
     st_b = torch.empty_like(d_expert)
     dis_d = mean_ms(lambda: fusco.fusco_disaggregated_dispatch(L, Lr, d_x, st_a, st_b, d_expert))
@@ -127,6 +131,7 @@ def time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, reps):
     return {"wire_rows_deduplicated": U, "wire_rows_one_per_pair": cfg.P, "wire_rows_ratio": U / cfg.P,
             "two_hop_dispatch_ms": two_hop, "two_hop_combine_ms": two_hop_c,
             "fused_dispatch_with_wire_tensor_ms": wire,
+            "wire_pack_deduplicated_ms": wire_only, "wire_pack_one_per_pair_ms": wire_no_dedup,
             "segments_scan_ms": seg_scan, "segments_pack_ms": seg_pack,
             "segments_pack_GBps": 2.0 * cap / (seg_pack * 1e-3) / 1e9, "segments_ok": seg_ok,
             "segments_pack_without_slices_ms": seg_pack_plain,
