@@ -140,6 +140,34 @@ def test_plan_is_deterministic(fusco):
         assert torch.equal(L.mem, ref)
 
 
+def test_movers_are_deterministic(fusco):
+    """Dispatch and combine (flat and along the two levels) give the same bytes on each of 20 runs: neither uses
+    atomics, every output element has one writer and a fixed order of operations."""
+    cfg = W.get_config("dsv3").with_tokens(2000)
+    A, w = W.make_routing(cfg)
+    x = bf16_dev(W.make_activations(cfg))
+    L, _ = gpu_plan(fusco, A, cfg.E, cfg.D)
+    d_w = dev(w)
+    eb = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+    sb = torch.empty((L.send_cap, cfg.H), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda")
+    out2 = torch.empty((cfg.N, cfg.H), dtype=torch.float32, device="cuda")
+    part = torch.zeros((L.send_cap, cfg.H), dtype=torch.float32, device="cuda")
+    U = int(L.array("send_off")[cfg.D].item())
+    ref = None
+    for _ in range(20):
+        eb.fill_(0); sb.fill_(0); out.fill_(0); out2.fill_(0)
+        fusco.fusco_dispatch(L, x, eb, send_buf=sb, flags=3)
+        fusco.fusco_combine(L, eb, d_w, out)
+        fusco.fusco_combine_two_hop(L, eb, d_w, part, out2)
+        torch.cuda.synchronize()
+        got = (eb.clone(), sb[:U].clone(), out.clone(), out2.clone(), part[:U].clone())
+        if ref is None:
+            ref = got
+        else:
+            assert all(torch.equal(a.view(torch.uint8), b.view(torch.uint8)) for a, b in zip(got, ref))
+
+
 @pytest.mark.parametrize("N", [700, 90000, 150000])          # one-level and chunked counts (352 tiles of 1024 pairs)
 def test_plan_counts_invalid_ids(fusco, oracle, N):
     rng = np.random.default_rng(77)
