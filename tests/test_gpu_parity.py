@@ -89,6 +89,58 @@ def test_plan_matches_oracle(fusco, oracle, N, k, E, D, distinct):
     assert got.U == want.U
 
 
+def _random_shape(rng):
+    k = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 31, 64]))
+    D = int(rng.choice([1, 2, 3, 4, 8, 16, 64]))
+    eloc = int(rng.choice([1, 2, 3, 8, 16]))
+    E = min(D * eloc, 1024)
+    D = E // eloc
+    distinct = bool(rng.integers(0, 2)) and k <= E
+    # around the planner's tile boundaries (1024 and 2048 pairs) as well as anywhere
+    tpt1 = 1024 // k
+    N = int(rng.choice([rng.integers(1, 4000), tpt1 * int(rng.integers(1, 6)) + int(rng.integers(-1, 2)),
+                        2 * tpt1 + int(rng.integers(-1, 2))]))
+    return max(N, 1), k, E, D, distinct
+
+
+def test_random_shapes_whole_path(fusco, oracle):
+    """300 random shapes (sizes, k, E, D, repeated or distinct experts, tile-boundary token counts): plan,
+    dispatch (expert and wire tensors) and combine against the oracle, element by element."""
+    rng = np.random.default_rng(20251127)
+    for case in range(300):
+        N, k, E, D, distinct = _random_shape(rng)
+        C = int(rng.choice([1, 2, 5, 16, 33, 64]))             # 16-byte units per row
+        A = random_topk(rng, N, k, E, distinct)
+        want = oracle.plan(A, E, D)
+        L, got = gpu_plan(fusco, A, E, D)
+        tag = "case %d: N=%d k=%d E=%d D=%d distinct=%s C=%d" % (case, N, k, E, D, distinct, C)
+        for f in PLAN_FIELDS:
+            assert np.array_equal(getattr(got, f), getattr(want, f)), (tag, f)
+        H = C * 8
+        xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
+        send_want, expert_want = oracle.dispatch(want, xb)
+        eb = torch.zeros((L.P, H), dtype=torch.bfloat16, device="cuda")
+        sb = torch.zeros((L.send_cap, H), dtype=torch.bfloat16, device="cuda")
+        fusco.fusco_dispatch(L, bf16_dev(xb), eb, send_buf=sb, flags=3)
+        w = rng.random((N, k)).astype(np.float32)
+        out = torch.zeros((N, H), dtype=torch.bfloat16, device="cuda")
+        fusco.fusco_combine(L, eb, dev(w), out)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits_host(eb), expert_want), tag
+        assert np.array_equal(bits_host(sb[:want.U]), send_want), tag
+        _, o16 = oracle.combine_f32(expert_want, w, want.pair_slot)
+        assert np.array_equal(bits_host(out), o16), tag
+        if N <= 2048 // k:                                      # the single-launch path gives the same
+            L2 = fusco.Layout(N, k, E, D)
+            eb2 = torch.zeros_like(eb)
+            fusco.fusco_plan_dispatch(L2, dev(A), bf16_dev(xb), eb2)
+            torch.cuda.synchronize()
+            got2 = L2.to_host()
+            for f in PLAN_FIELDS:
+                assert np.array_equal(getattr(got2, f), getattr(want, f)), (tag, "fused", f)
+            assert torch.equal(eb2, eb), tag
+
+
 def test_plan_empty_input(fusco, oracle):
     L, got = gpu_plan(fusco, np.zeros((0, 4), dtype=np.int32), 8, 2)
     assert got.exp_off.tolist() == [0] * 9 and got.send_off.tolist() == [0] * 3
