@@ -326,7 +326,7 @@ def main() -> int:
 
     # decode-sized inputs (one planner tile): the same step with plan and dispatch in one launch
     fused = None
-    if cfg.N <= 2048 // cfg.k and len(sets) == 1 and not args.graph:
+    if cfg.N <= 2048 // cfg.k and len(sets) == 1:
         def fused_step():
             fusco.fusco_plan_dispatch(L, d_A, d_x, d_expert, **{k_: v for k_, v in dispatch_kwargs.items()})
             fusco.fusco_combine(L, d_y, d_w, d_out)
@@ -338,13 +338,28 @@ def main() -> int:
         if not (torch.equal(L.mem, want_layout) and torch.equal(d_expert, want_expert)):
             print("bench.py: fused plan + dispatch differs from the two calls", file=sys.stderr)
             return 1
+        run_fused, how = fused_step, "fusco_plan_dispatch + fusco_combine"
+        if args.graph:
+            side2 = torch.cuda.Stream()
+            side2.wait_stream(torch.cuda.current_stream())
+            fgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side2):
+                with torch.cuda.graph(fgraph, stream=side2):
+                    fused_step()
+            torch.cuda.current_stream().wait_stream(side2)
+            d_expert.zero_()
+            fgraph.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(d_expert, want_expert):
+                print("bench.py: graph replay of the fused step differs", file=sys.stderr)
+                return 1
+            run_fused, how = fgraph.replay, how + ", one HIP graph replay per step"
         t0 = time.perf_counter()
         for _ in range(K):
-            fused_step()
+            run_fused()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        fused = {"ms_per_step": dt * 1e3 / K, "tokens_per_s": cfg.N * K / dt,
-                 "launches": "fusco_plan_dispatch + fusco_combine"}
+        fused = {"ms_per_step": dt * 1e3 / K, "tokens_per_s": cfg.N * K / dt, "launches": how}
 
     ceilings = None
     if not args.no_ceilings and cfg.payload == "bf16":
