@@ -54,7 +54,7 @@ extern "C" {
 
 /*
  * Layout descriptor: the two-level descriptor lists of the paper's Communication Planner
- * (section 3.3, "Descriptor-level communication plan") for fixed-size segments.  A segment is one
+ * (section 3.3, the paragraph on the descriptor-level plan) for fixed-size segments.  A segment is one
  * token row, so a segment descriptor (address, size) collapses to a row index.
  *
  * N tokens, k experts per token, E experts, D devices, P = N * k (token, expert) pairs.
@@ -153,7 +153,7 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
                         void *stream);
 
 /*
- * Weighted combine (reverse path of the shuffle; "combined through a weighted summation",
+ * Weighted combine (reverse path of the shuffle: weighted sum of a token's expert outputs,
  * section 2.1):   out[t, :] = sum_{j=0..k-1} w[t, j] * y[pair_slot[t*k+j], :]
  * accumulated in fp32 with one fused multiply-add per term in ascending j from +0, then rounded
  * once (nearest even) when out_dtype is FUSCO_BF16.
@@ -206,6 +206,19 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
                                 int32_t H, void *stream);
 
 /*
+ * Input of the load balancer (section 3.4): the cross-node traffic load of the GPU that owns this plan,
+ * i.e. the volume it must transmit to remote nodes.  The D destination devices are grouped into nodes of
+ * devices_per_node consecutive devices (D must be a multiple); the GPU itself sits on node home_node.
+ *     *d_load = row_bytes * sum of send_count[d] over the devices d with d / devices_per_node != home_node
+ * in bytes, after duplicate removal (one send row per token and destination device; plan with D = number
+ * of nodes for the paper's one copy per node).  d_load: one int64 in device memory, 8-byte aligned, e.g. the
+ * GPU's cell of the [nodes, gpus] matrix that fusco_balance_groups takes once every GPU has filled its own.
+ * Must follow the fusco_plan of the same layout in stream order.  One small launch.
+ */
+int fusco_cross_node_load(const fusco_layout *L, int32_t devices_per_node, int32_t home_node, size_t row_bytes,
+                          int64_t *d_load, void *stream);
+
+/*
  * Online Group-Balanced Assignment (Algorithm 1, section 3.4).  Host-only, no GPU work.
  * load: [nodes, gpus] row-major, cross-node traffic load of every GPU.  For every node the GPUs are
  * sorted by descending load (equal loads keep ascending GPU index), the sorted list is rotated by
@@ -248,52 +261,19 @@ int fusco_segments_scan(const fusco_segment *d_desc, int64_t n, uint64_t *d_cum,
  * host (the exact total is read on the device from d_cum[n]).
  * Slices: if d_slice_fill is given, the contiguous stream is cut into slices of slice_bytes (a
  * multiple of 16384) and d_slice_fill[s] counts the bytes of slice s that have been written and are
- * visible; it is reset to 0 at the start of the call.  A consumer takes slice s once the count
- * reaches min(slice_bytes, total - s * slice_bytes).
+ * visible: the data is stored write-through at system scope, every workgroup waits for its stores
+ * and only then adds its bytes with a system-scope atomic.  A consumer (another stream, another
+ * agent) takes slice s once the count reaches min(slice_bytes, total - s * slice_bytes); it must
+ * read the counter with an acquire (or bypass its caches for the slice's bytes).  Units skipped for
+ * being out of range are not counted, so a slice with holes never becomes ready.  The counters are
+ * reset to 0 by a small kernel at the start of the call, in stream order: a consumer that is still
+ * polling the counters of the previous call on the same d_slice_fill races with that reset; give
+ * overlapping transfers counter arrays of their own.
  */
 int fusco_segments_copy(const void *d_src, uint64_t src_bytes, const fusco_segment *d_src_desc, void *d_dst,
                         uint64_t dst_bytes, const fusco_segment *d_dst_desc, const uint64_t *d_cum, int64_t n,
                         uint64_t stream_capacity, uint64_t slice_bytes, uint32_t *d_slice_fill, int32_t *d_status,
                         void *stream);
-
-/*
- * Measurement aid: plain device copy of `bytes` bytes (multiple of 16) with the same 16-byte
- * accesses the shuffle kernels use.  Used to calibrate hardware traffic counters and as the
- * copy ceiling next to the shuffle's bandwidth.
- */
-int fusco_probe_copy(void *d_dst, const void *d_src, size_t bytes, void *stream);
-
-/*
- * Measurement aid: whole-row traffic of a chosen shape, with no plan behind it and no arithmetic.
- * One workgroup reads `reads_per_group` rows of d_src (XOR-ing them) and writes `writes_per_group`
- * rows of d_dst; supported shapes (reads, writes): (0,1) fill, (1,0) read, (1,1) copy, (1,8) the
- * dispatch mix, (8,1) the combine mix.  The grid is dst_rows / writes_per_group workgroups (for
- * (1,0): src_rows); dst_rows must be a multiple of writes_per_group and src_rows must hold
- * groups * reads_per_group rows.  scatter == 0 walks both buffers in launch order; otherwise row i of
- * a stream sits at (i * m) mod rows with m coprime to the row count, i.e. rows land far from their
- * launch-order neighbours as they do under routing.  write_through != 0 uses the write-through stores
- * of the combine kernel, else plain stores.  d_sink (one uint32 in device memory) is needed for
- * (1,0) only and is never written in practice.  Buffers: [src_rows, row_bytes], [dst_rows,
- * row_bytes], 16-byte aligned, row_bytes a multiple of 16.  Returns FUSCO_ERR_INVALID_ARG otherwise.
- */
-int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t dst_rows, size_t row_bytes,
-                     int reads_per_group, int writes_per_group, int scatter, int write_through,
-                     uint32_t *d_sink, void *stream);
-
-/*
- * Measurement aid: kernel time without stream events between the kernels.  The next fusco_plan,
- * fusco_dispatch (fused modes), fusco_plan_dispatch or fusco_combine call made by the calling thread attaches the two HIP
- * events (hipEvent_t passed as void*, created with timing enabled) to its own kernels: start_event
- * is recorded when the call's first kernel begins, stop_event when its last kernel ends, both from
- * the kernels' own dispatch timestamps.  hipEventElapsedTime(start, stop) after the stream has been
- * synchronised is then the device time of that call, as a profiler's kernel trace reports it; a
- * pair of hipEventRecord calls around the launch would add the cost of the barriers they put into
- * the stream.  The arming is per thread and is used up by the first such call that launches
- * kernels (a call that fails its argument checks or has an empty layout leaves it armed;
- * FUSCO_DISPATCH_TWO_HOP uses it up without recording).  Events are not recorded into a stream
- * that is being captured: do not arm before a captured call.
- */
-int fusco_probe_time_next_call(void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

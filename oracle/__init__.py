@@ -22,14 +22,24 @@ _LIB = os.path.join(_HERE, "libfusco_oracle.so")
 BF16, F32 = 0, 1
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, no contraction so that only the explicit fmaf fuses)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fPIC", "-shared",
-                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+_LIB_SANITIZED = os.path.join(_HERE, "libfusco_oracle_sanitized.so")
+# set in the environment of a process that has the AddressSanitizer runtime preloaded: the oracle is then the
+# instrumented build (tests/test_oracle_sanitized.py runs the pins that way)
+SANITIZED_ENV = "FUSCO_ORACLE_SANITIZED"
+
+
+def build(force: bool = False, sanitized: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no contraction so that only the explicit fmaf fuses).
+    sanitized: the same source with AddressSanitizer and UndefinedBehaviorSanitizer, as a library of its own."""
+    lib = _LIB_SANITIZED if sanitized else _LIB
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC):
+        tmp = lib + ".tmp%d" % os.getpid()
+        extra = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                 "-fno-sanitize-recover=all"] if sanitized else ["-O2"]
+        subprocess.check_call(["gcc", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-Wextra"]
+                              + extra + ["-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, lib)
+    return lib
 
 
 _lib = None
@@ -38,7 +48,7 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        _lib = ctypes.CDLL(build(sanitized=os.environ.get(SANITIZED_ENV) == "1"))
         for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_dispatch_rows",
                      "fusco_oracle_combine_f64",
                      "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64",
@@ -212,6 +222,20 @@ def combine_two_hop_f32(pl: Plan, y: np.ndarray, w: np.ndarray, tokens=None, wan
     if rc != 0:
         raise ValueError("fusco_oracle_combine_two_hop_f32 failed with code %d" % rc)
     return (o32, o16, part) if want_partial else (o32, o16)
+
+
+def cross_node_load(topk_idx: np.ndarray, E: int, D: int, devices_per_node: int, home_node: int, row_bytes: int) -> int:
+    """Cross-node traffic load of one GPU (paper section 3.4: the volume it must transmit to remote nodes),
+    counted from the routing itself: every token sends one row of row_bytes to each distinct destination
+    device (experts placed in contiguous blocks of E / D), and only devices on another node than the GPU's
+    own count.  Plain loops over the token-expert matrix; no use of the planner's arrays."""
+    A = np.asarray(topk_idx)
+    eloc = E // D
+    total = 0
+    for t in range(A.shape[0]):
+        devices = set(int(e) // eloc for e in A[t])
+        total += sum(1 for d in devices if d // devices_per_node != home_node)
+    return total * int(row_bytes)
 
 
 def balance_groups(load) -> np.ndarray:

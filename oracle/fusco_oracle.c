@@ -6,8 +6,8 @@
  * in the product may call it: only the tests, the smoke check and the benchmark's CPU-baseline
  * leg do.
  *
- * What it follows (paper section "Communication Planner", paragraph "Descriptor-level
- * communication plan", and section "Data-Fused Communication Engine"):
+ * What it follows (paper section 3.3, the paragraph on the descriptor-level plan, and section 3.2,
+ * the transfer engine):
  *   - A is the token-expert matrix (T x K): the experts the router assigned to each token.
  *   - B is the token-node matrix derived from A under a fixed expert placement.  Here a "node"
  *     is one virtual expert-parallel device, experts are placed in contiguous blocks, so the
@@ -22,11 +22,11 @@
  *   - The transfer engine moves each segment (one token row) from the address in the send
  *     descriptor to the address in the receive descriptor.
  *   - The reverse path restores token order; the expert outputs of a token are combined by a
- *     weighted sum (section "Mixture-of-Experts Models").
+ *     weighted sum (section 2.1).
  *
  * Readings where the paper is silent:
  *   - rows inside one expert's segment, and inside one device's receive tensor, are in
- *     ascending token order (the planner "iterates" over tokens and appends);
+ *     ascending token order (the planner walks the tokens and appends);
  *   - the receive tensors of the D devices are laid out one after the other (device-major), and
  *     so are the expert segments (device-major, then expert-major: with contiguous placement
  *     this is plain ascending expert id);
@@ -321,7 +321,7 @@ int fusco_oracle_combine_abs_f64(const void *y, int y_dtype, const float *w, con
 }
 
 /*
- * Combine along the two descriptor levels in reverse (the "symmetric reverse" of the two-hop
+ * Combine along the two descriptor levels in reverse (the mirror of the two-hop
  * dispatch; the paper gives no arithmetic for it, this is the reading used here):
  *   level 2 reversed: every send row r = (token t, device d) receives the partial sum of the
  *     token's entries on that device, partial[r] = sum_{j : dev(A[t][j]) = d} w[t][j] * y[slot(t,j)],
@@ -371,8 +371,7 @@ int fusco_oracle_combine_two_hop_f32(const void *y, int y_dtype, const float *w,
 }
 
 /*
- * Segment-descriptor transfer (section "Data-Fused Communication Engine", paragraph "Segment
- * descriptor"): a payload is a sequence of n logical segments; segment i is size[i] bytes long and
+ * Segment-descriptor transfer (section 3.2, the paragraph on segment descriptors): a payload is a sequence of n logical segments; segment i is size[i] bytes long and
  * lies at src_off[i] in the sender's memory and at dst_off[i] in the receiver's.  The descriptor
  * lists are dense arrays in transfer order and map one to one.  A NULL offset list means that side
  * is the contiguous stream itself (segment i starts at the cumulative size of the segments before

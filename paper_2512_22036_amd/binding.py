@@ -22,7 +22,7 @@ _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
            "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
-           "fusco_combine_two_hop", "fusco_balance_groups", "fusco_segments_scan", "fusco_segments_copy",
+           "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
 
@@ -90,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_segments_scan.argtypes = [vp, i64, vp, vp, vp]
     lib.fusco_segments_copy.restype = ctypes.c_int
     lib.fusco_segments_copy.argtypes = [vp, u64, vp, vp, u64, vp, vp, i64, u64, u64, vp, vp, vp]
+    lib.fusco_cross_node_load.restype = ctypes.c_int
+    lib.fusco_cross_node_load.argtypes = [ctypes.POINTER(_CLayout), i32, i32, sz, vp, vp]
     lib.fusco_balance_groups.restype = ctypes.c_int
     lib.fusco_balance_groups.argtypes = [vp, i32, i32, vp]
     lib.fusco_combine_two_hop.restype = ctypes.c_int
@@ -271,6 +273,15 @@ def fusco_combine_two_hop(layout: Layout, y: torch.Tensor, w: torch.Tensor, part
                                                 w.data_ptr(), partial.data_ptr(), out.data_ptr(),
                                                 _dtype_code(out, "out"), H, _stream(stream)),
            "fusco_combine_two_hop")
+
+
+def fusco_cross_node_load(layout: Layout, devices_per_node: int, home_node: int, row_bytes: int,
+                          load: torch.Tensor, stream=None) -> None:
+    """load: one-element int64 device tensor (e.g. a cell of the [nodes, gpus] load matrix)."""
+    if not load.is_cuda or load.dtype != torch.int64 or load.numel() != 1:
+        raise FuscoError("load must be a one-element int64 device tensor")
+    _check(load_library().fusco_cross_node_load(ctypes.byref(layout.c), devices_per_node, home_node, row_bytes,
+                                                load.data_ptr(), _stream(stream)), "fusco_cross_node_load")
 
 
 def fusco_balance_groups(load) -> "numpy.ndarray":

@@ -7,6 +7,7 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include "fusco.h"
+#include "fusco_probe.h"
 
 namespace {
 

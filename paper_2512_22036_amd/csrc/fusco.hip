@@ -294,7 +294,7 @@ int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, c
 int fusco_disaggregated_plan(fusco_layout *Lr, const fusco_layout *L, const int32_t *d_topk_idx, int32_t *d_topk_dev,
                              void *d_scratch, size_t scratch_bytes, void *stream)
 {
-    if (!layout_ok(L) || !layout_ok(Lr) || (!d_topk_idx && L->N > 0) || (!d_topk_dev && L->N > 0))
+    if (!layout_ok(L) || !layout_ok(Lr) || (!d_topk_idx && L->N > 0) || (!d_topk_dev && L->N > 0) || !d_scratch)
         return FUSCO_ERR_INVALID_ARG;
     if (Lr->N != L->N || Lr->k != L->k || Lr->E != L->D || Lr->D != L->D) return FUSCO_ERR_INVALID_ARG;
     if (scratch_bytes < fusco_scratch_bytes(Lr->N, Lr->k, Lr->E, Lr->D)) return FUSCO_ERR_WORKSPACE;
@@ -343,6 +343,18 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
     launch_gather<true>(d_y, d_stage_b, Lr->slot_pair, L->pair_slot, Lr->exp_off + Lr->E, L->P, (int)(row_bytes / 16), s);
     launch_copy(d_stage_a, d_stage_b, (size_t)L->P * row_bytes, s);
     combine_launch(Lr->pair_slot, L->N, L->k, d_stage_a, y_dtype, d_w, d_out, out_dtype, H, s);
+    return launch_status();
+}
+
+int fusco_cross_node_load(const fusco_layout *L, int32_t devices_per_node, int32_t home_node, size_t row_bytes,
+                          int64_t *d_load, void *stream)
+{
+    if (!layout_ok(L) || !d_load || ((uintptr_t)d_load & 7u)) return FUSCO_ERR_INVALID_ARG;
+    if (devices_per_node < 1 || L->D % devices_per_node != 0) return FUSCO_ERR_INVALID_ARG;
+    if (home_node < 0 || home_node >= L->D / devices_per_node) return FUSCO_ERR_INVALID_ARG;
+    if (row_bytes == 0 || row_bytes > FUSCO_MAX_ROW_BYTES) return FUSCO_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(cross_node_load_kernel, dim3(1), dim3(kWave), 0, (hipStream_t)stream, L->send_count, L->D,
+                       devices_per_node, home_node, (uint64_t)row_bytes, d_load);
     return launch_status();
 }
 

@@ -16,8 +16,9 @@ namespace {
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ u32x4 load16_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 
-// 16-byte / 8-byte stores that go to memory at system scope instead of lingering in the L2:
-// used for the token-ordered output of combine, which is never read again by this kernel.
+// 16-byte / 8-byte write-through stores at device scope (sc1): the data leaves the L2 of the XCD for
+// memory instead of lingering there.  Used for the token-ordered output of combine, which is never
+// read again by this kernel.
 // The s_nop supplies the wait states gfx9 needs between a store of more than 8 bytes and a
 // following VALU write to its data registers; the compiler adds them for its own stores but
 // cannot see into this statement.
@@ -28,6 +29,11 @@ __device__ __forceinline__ void store16_through(u32x4 *p, u32x4 v)
 __device__ __forceinline__ void store8_through(u32x2 *p, u32x2 v)
 {
     asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+}
+// The same at system scope (sc0 sc1): for data that another agent may read once a flag says so.
+__device__ __forceinline__ void store16_system(u32x4 *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
 // Dispatch: the row is held in registers between the single read and the k (+ wire) writes.

@@ -400,6 +400,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_place_kernel(PlanArgs a)
     place_tile<SINGLE, R>(s, a, blockIdx.x, true);
 }
 
+// Cross-node traffic load of the GPU that owns this plan (section 3.4): bytes of the send rows whose
+// destination device lies on another node than `home_node`.  One wave.
+__global__ __launch_bounds__(kWave) void cross_node_load_kernel(const int32_t *send_count, int D, int devices_per_node,
+                                                               int home_node, uint64_t row_bytes, int64_t *load)
+{
+    int64_t rows = 0;
+    for (int d = threadIdx.x; d < D; d += kWave)
+        if (d / devices_per_node != home_node) rows += send_count[d];
+    for (int s = kWave / 2; s > 0; s >>= 1) rows += __shfl_down(rows, s, kWave);
+    if (threadIdx.x == 0) *load = rows * (int64_t)row_bytes;
+}
+
 }   // namespace
 
 #endif

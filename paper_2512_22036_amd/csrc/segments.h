@@ -100,7 +100,11 @@ __global__ __launch_bounds__(kSegThreads) void segments_copy_kernel(SegCopyArgs 
         const uint64_t intra = pos - a.cum[i];
         const uint64_t so = a.src_desc ? a.src_desc[i].offset + intra : pos;
         const uint64_t dofs = a.dst_desc ? a.dst_desc[i].offset + intra : pos;
-        if (((so | dofs) & 15u) || so + 16 > a.src_bytes || dofs + 16 > a.dst_bytes) {
+        // in range without any sum that could wrap: a unit fits iff its start is at most bytes - 16, and a
+        // start below `intra` means offset + intra wrapped around 2^64 (e.g. a negative offset)
+        const bool src_in = a.src_bytes >= 16 && so <= a.src_bytes - 16 && so >= intra;
+        const bool dst_in = a.dst_bytes >= 16 && dofs <= a.dst_bytes - 16 && dofs >= intra;
+        if (((so | dofs) & 15u) || !src_in || !dst_in) {
             ++skipped;
             continue;
         }
@@ -111,22 +115,27 @@ __global__ __launch_bounds__(kSegThreads) void segments_copy_kernel(SegCopyArgs 
 #pragma unroll
     for (int r = 0; r < kSegUnits; ++r) {
         if (!ok[r]) continue;
-        if constexpr (SLICES) store16_through((u32x4 *)(a.dst + dst_at[r]), v[r]);
+        if constexpr (SLICES) store16_system((u32x4 *)(a.dst + dst_at[r]), v[r]);
         else *(u32x4 *)(a.dst + dst_at[r]) = v[r];
     }
     if (skipped) atomicAdd(a.status, skipped);
     if constexpr (SLICES) {
-        // A slice counts bytes only once they are in memory: the stores above go through the L2 at
-        // system scope, every thread waits for its own to complete, and only then one thread adds
-        // the workgroup's bytes with a system-scope atomic.  (A device-wide release fence would do
-        // too, but it writes back the whole L2 of the XCD each time.)
+        // A slice counts bytes only once they are in memory: the stores above are write-through at
+        // system scope (sc0 sc1), every thread waits for its own to complete, and only then one thread
+        // adds the bytes the workgroup has really written (skipped units are left out, so a slice with
+        // holes never reaches its size) with a system-scope atomic.  (A device-wide release fence
+        // would do too, but it writes back the whole L2 of the XCD each time.)
+        __shared__ int skipped_total;
+        if (threadIdx.x == 0) skipped_total = 0;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (skipped) atomicAdd(&skipped_total, skipped);
         __syncthreads();
         if (threadIdx.x == 0) {
             const uint64_t left = total - base;
-            __hip_atomic_fetch_add(a.slice_fill + base / a.slice_bytes,
-                                   (uint32_t)(left < kSegBlockBytes ? left : kSegBlockBytes), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_SYSTEM);
+            const uint32_t mine = (uint32_t)(left < kSegBlockBytes ? left : kSegBlockBytes);
+            __hip_atomic_fetch_add(a.slice_fill + base / a.slice_bytes, mine - 16u * (uint32_t)skipped_total,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
 }

@@ -101,3 +101,48 @@ def test_library_rejects_bad_arguments():
     assert lib.fusco_balance_groups(buf, 0, 2, out) == -1
     assert lib.fusco_balance_groups(buf, 2, 0, out) == -1
     assert lib.fusco_balance_groups(buf, 1 << 20, 1 << 10, out) == -1
+
+
+# ---- the balancer's input: cross-node traffic load of a GPU, from its routing (section 3.4) ----
+
+def _load_golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "cross_node_load_hand_example.txt")
+    kv, tokens, loads = {}, [], {}
+    for line in open(path):
+        if line.startswith("#") or ":" not in line:
+            continue
+        key, val = line.split(":")
+        if key == "token":
+            tokens.append([int(v) for v in val.split()])
+        elif key == "load_from_node":
+            n, b = val.split()
+            loads[int(n)] = int(b)
+        else:
+            kv[key] = int(val)
+    return kv, np.array(tokens, dtype=np.int32), loads
+
+
+def test_cross_node_load_hand_worked_example(oracle):
+    kv, A, loads = _load_golden()
+    for node, want in loads.items():
+        assert oracle.cross_node_load(A, kv["E"], kv["D"], kv["devices_per_node"], node, kv["row_bytes"]) == want
+
+
+def test_cross_node_load_special_cases_and_plan_relation(oracle):
+    from definitions import random_topk
+    rng = np.random.default_rng(21)
+    for N, k, E, D, dpn in [(50, 4, 16, 8, 2), (33, 8, 64, 8, 4), (20, 2, 6, 6, 1), (40, 3, 12, 4, 4), (10, 5, 10, 1, 1)]:
+        A = random_topk(rng, N, k, E)
+        pl = oracle.plan(A, E, D)
+        nodes = D // dpn
+        total = 0
+        for home in range(nodes):
+            got = oracle.cross_node_load(A, E, D, dpn, home, 16)
+            # the same count read off the planner's per-device send rows (built by list appends, not by sets)
+            remote = sum(int(pl.send_count[d]) for d in range(D) if d // dpn != home)
+            assert got == 16 * remote
+            total += got
+        # over all home nodes every send row is remote for all nodes but its own
+        assert total == 16 * pl.U * (nodes - 1)
+        if nodes == 1:
+            assert total == 0                      # a single node has no cross-node traffic

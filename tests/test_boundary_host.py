@@ -8,7 +8,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "fusco.h")
+HEADER = os.path.join(ROOT, "include", "fusco.h")              # the shuffle's boundary and its variants
+PROBE_HEADER = os.path.join(ROOT, "include", "fusco_probe.h")  # measurement aids of the same library
 
 
 @pytest.fixture(scope="module")
@@ -21,8 +22,11 @@ def lib():
 
 
 def _declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
-    return sorted(set(re.findall(r"\b(fusco_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in (HEADER, PROBE_HEADER):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(fusco_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_functions_are_exported(lib):
@@ -37,13 +41,14 @@ def test_header_is_plain_c_and_cxx():
     """The boundary is a C header: it must compile on its own as C99 and as C++ (no HIP or torch types)."""
     import shutil
     import subprocess
-    header = os.path.join(ROOT, "include", "fusco.h")
     if not shutil.which("gcc") or not shutil.which("g++"):
         pytest.skip("no host compiler")
-    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header])
-    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header])
-    text = open(header).read()
-    assert "hip/" not in text and "torch" not in text.lower()
+    for header in (HEADER, PROBE_HEADER):
+        subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header])
+        subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header])
+        text = open(header).read()
+        assert "hip/" not in text and "torch" not in text.lower()
+    assert "probe" not in open(HEADER).read().lower()      # the aids stay out of the shuffle's header
 
 
 def test_version_and_status_strings(lib):
@@ -192,6 +197,17 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert dc(buf, 0, buf, buf, buf, None, 0, 64, None) == -1
     assert dc(buf, 3, buf, buf, buf, buf, 0, 64, None) == -3
     assert dc(buf, 0, buf, buf, buf, buf, 0, 12, None) == -1
+    assert lib.fusco_disaggregated_plan(ctypes.byref(Lr), ctypes.byref(L), buf, buf, None, rscratch, None) == -1  # no scratch
+    # cross-node load of the balancer
+    cl = lambda *a: lib.fusco_cross_node_load(ctypes.byref(L), *a)
+    assert cl(2, 0, 64, None, None) == -1                     # no result cell
+    assert cl(2, 0, 64, buf + 4, None) == -1                  # misaligned cell
+    assert cl(3, 0, 64, buf, None) == -1                      # D = 4 is not a multiple of 3
+    assert cl(0, 0, 64, buf, None) == -1
+    assert cl(2, 2, 64, buf, None) == -1                      # only nodes 0 and 1 exist
+    assert cl(2, -1, 64, buf, None) == -1
+    assert cl(2, 0, 0, buf, None) == -1
+    assert lib.fusco_cross_node_load(None, 2, 0, 64, buf, None) == -1
     # probe copy
     assert lib.fusco_probe_copy(None, buf, 64, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4, 64, None) == -1

@@ -95,3 +95,51 @@ def test_invalid_descriptors_are_counted_and_skipped(fusco):
     torch.cuda.synchronize()
     assert int(status.item()) == 2 + 4                      # four 16-byte units of the out-of-range segment
     assert torch.equal(dst[:64], src[:64]) and bool((dst[64:] == 0xEE).all())
+
+
+def test_offsets_that_wrap_are_counted_and_touch_nothing(fusco):
+    """Offsets whose sum with the position inside the segment leaves the buffer, or wraps around 2^64 (a negative
+    int64, a huge value), are skipped unit by unit: nothing is read or written through them, the rows next to the
+    buffer stay as they were, and a slice with such holes does not reach its size."""
+    seg = 64
+    good = np.array([0, 128], dtype=np.int64)
+    bad = np.array([-16, -64, np.iinfo(np.int64).min, np.iinfo(np.int64).max - 15, 1 << 40], dtype=np.int64)
+    off = np.concatenate([good[:1], bad, good[1:]])             # 7 segments of 64 bytes, 5 of them wild
+    size = np.full(len(off), seg, dtype=np.int64)
+    d = desc_dev(off, size)
+    cum, status = scan(fusco, d)
+    assert int(status.item()) == 0                               # aligned offsets and sizes: the scan accepts them
+    total = seg * len(off)
+    # the buffers are windows in the middle of larger allocations, so that a write or a read just outside
+    # would hit memory we own and can inspect
+    room = torch.full((3, 4096), 0x5A, dtype=torch.uint8, device="cuda")
+    src = room[1, :256]
+    src.copy_(torch.arange(256, dtype=torch.uint8, device="cuda"))
+    out_room = torch.full((3, 16384), 0xEE, dtype=torch.uint8, device="cuda")
+    packed = out_room[1]
+    fill = torch.full((1,), 77, dtype=torch.int32, device="cuda")
+    fusco.fusco_segments_copy(src, d, packed, None, cum, 16384, status, slice_bytes=16384, slice_fill=fill)
+    torch.cuda.synchronize()
+    units_bad = len(bad) * seg // 16
+    assert int(status.item()) == units_bad
+    got = packed.cpu().numpy()
+    want = np.full(16384, 0xEE, dtype=np.uint8)
+    want[0:64] = np.arange(0, 64)
+    want[6 * seg:7 * seg] = np.arange(128, 192)
+    assert np.array_equal(got, want)
+    assert bool((out_room[0] == 0xEE).all()) and bool((out_room[2] == 0xEE).all())
+    assert int(fill.item()) == total - 16 * units_bad           # holes are not counted: the slice is not ready
+    # receiver side: the same wild offsets as destinations
+    status.zero_()
+    dst = out_room[1, :256]
+    out_room.fill_(0xEE)
+    stream_in = torch.arange(total, dtype=torch.int32, device="cuda").to(torch.uint8)
+    fusco.fusco_segments_copy(stream_in, None, dst, d, cum, total, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == units_bad
+    want = np.full(256, 0xEE, dtype=np.uint8)
+    want[0:64] = np.arange(0, 64)
+    want[128:192] = (np.arange(6 * seg, 7 * seg) % 256).astype(np.uint8)
+    assert np.array_equal(dst.cpu().numpy(), want)
+    assert bool((out_room[0] == 0xEE).all()) and bool((out_room[2] == 0xEE).all()) and bool((out_room[1, 256:] == 0xEE).all())
+    assert bool((room[0] == 0x5A).all()) and bool((room[2] == 0x5A).all())

@@ -248,3 +248,40 @@ def test_plain_c_program_uses_the_boundary_without_python(fusco):
         build.build_c_example()          # host compiler only, a second or two
     res = subprocess.run([build.EXAMPLE_BIN], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=100)
     assert res.returncode == 0 and "c_abi_usage ok" in res.stdout, res.stdout
+
+
+def test_cross_node_load_matrix_feeds_the_balancer(fusco, oracle):
+    """Section 3.4 end to end: every GPU of a 2-node x 4-GPU cluster plans its own (skewed) routing, writes its
+    cross-node load into its cell of the device-resident load matrix, and Algorithm 1 groups the GPUs."""
+    import dataclasses
+    import workloads as W
+    nodes, gpus, row_bytes = 2, 4, 14336
+    base = W.get_config("skewed").with_tokens(1500)
+    matrix = torch.full((nodes, gpus), -1, dtype=torch.int64, device="cuda")
+    want = np.zeros((nodes, gpus), dtype=np.int64)
+    for n in range(nodes):
+        for g in range(gpus):
+            cfg = dataclasses.replace(base, seed=base.seed + 17 * (n * gpus + g))
+            A, _ = W.make_routing(cfg)
+            L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+            fusco.fusco_plan(L, torch.from_numpy(A).cuda())
+            fusco.fusco_cross_node_load(L, cfg.D // nodes, n, row_bytes, matrix[n, g:g + 1])
+            want[n, g] = oracle.cross_node_load(A, cfg.E, cfg.D, cfg.D // nodes, n, row_bytes)
+    torch.cuda.synchronize()
+    got = matrix.cpu().numpy()
+    assert np.array_equal(got, want)
+    assert len(set(want.ravel().tolist())) > 1                 # the skewed routing does load the GPUs unevenly
+    assert np.array_equal(fusco.fusco_balance_groups(got), oracle.balance_groups(want))
+    # one device per node: the load is everything but the GPU's own device
+    cfg = base
+    A, _ = W.make_routing(cfg)
+    L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+    fusco.fusco_plan(L, torch.from_numpy(A).cuda())
+    cell = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for home in (0, cfg.D - 1):
+        fusco.fusco_cross_node_load(L, 1, home, 16, cell)
+        torch.cuda.synchronize()
+        assert int(cell.item()) == oracle.cross_node_load(A, cfg.E, cfg.D, 1, home, 16)
+    fusco.fusco_cross_node_load(L, cfg.D, 0, 16, cell)        # a single node: nothing crosses
+    torch.cuda.synchronize()
+    assert int(cell.item()) == 0

@@ -306,3 +306,57 @@ def test_two_hop_combine_error_bound_and_subset(oracle):
     toks = np.array([99, 0, 5], dtype=np.int32)
     s32, s16 = oracle.combine_two_hop_f32(pl, y, w, tokens=toks)
     assert np.array_equal(s32, h32[toks]) and np.array_equal(s16, h16[toks])
+
+
+# ---- one rounding per term: the fused multiply-add of the single-precision chain ----
+# Hand-worked.  Term 0 puts acc = -y0 exactly (w = 1).  Term 1 has an exact product w1 * y1 that needs one
+# bit more than single precision holds, and that bit survives only if the product is not rounded before
+# the addition:
+#   float32 y:  w1 = y1 = 1 + 2^-12      product = 1 + 2^-11 + 2^-24   (2^-24 is half an ulp of 1: a tie that
+#               rounds to the even neighbour 1 + 2^-11)   y0 = -1
+#               fused:   -1 + (1 + 2^-11 + 2^-24) = 2^-11 + 2^-24     multiply, round, add: 2^-11
+#   bfloat16 y: y1 = 1 + 2^-7 (8 significant bits), w1 = 1 + 2^-17   product = 1 + 2^-7 + 2^-17 + 2^-24
+#               y0 = -(1 + 2^-7)   fused: 2^-17 + 2^-24               multiply, round, add: 2^-17
+# Rounded to bfloat16 (8 significant bits): 2^-11 (1 + 2^-13) -> 2^-11;  2^-17 (1 + 2^-7) is exact.
+FMA_F32 = dict(y0=-1.0, y1=1.0 + 2.0 ** -12, w1=1.0 + 2.0 ** -12, fused=2.0 ** -11 + 2.0 ** -24, unfused=2.0 ** -11,
+               bf16_out=2.0 ** -11)
+FMA_BF16 = dict(y0=-(1.0 + 2.0 ** -7), y1=1.0 + 2.0 ** -7, w1=1.0 + 2.0 ** -17, fused=2.0 ** -17 + 2.0 ** -24,
+                unfused=2.0 ** -17, bf16_out=2.0 ** -17 + 2.0 ** -24)
+
+
+def _fma_case(case, as_bf16):
+    y = np.array([[case["y0"]], [case["y1"]]], dtype=np.float32)
+    if as_bf16:
+        bits = W.bf16_bits(y)
+        assert np.array_equal(W.bf16_bits_to_f32(bits), y)          # both values are exact in bfloat16
+        y = bits
+    w = np.array([[1.0, case["w1"]]], dtype=np.float32)
+    assert float(w[0, 1]) == case["w1"]                             # and the weight is exact in float32
+    return y, w
+
+
+@pytest.mark.parametrize("case,as_bf16", [(FMA_F32, False), (FMA_BF16, True)])
+def test_combine_f32_rounds_once_per_term(oracle, case, as_bf16):
+    y, w = _fma_case(case, as_bf16)
+    f32, b16 = oracle.combine_f32(y, w, np.array([0, 1], dtype=np.int32))
+    assert float(f32[0, 0]) == case["fused"] and float(f32[0, 0]) != case["unfused"]
+    # the bfloat16 output is the nearest bfloat16 of that sum
+    assert np.array_equal(W.bf16_bits_to_f32(b16), np.array([[case["bf16_out"]]], dtype=np.float32))
+    # the double-precision sum is exact here and agrees with the fused result
+    assert float(oracle.combine_f64(y, w, np.array([0, 1], dtype=np.int32))[0, 0]) == case["fused"]
+
+
+@pytest.mark.parametrize("case,as_bf16", [(FMA_F32, False), (FMA_BF16, True)])
+def test_two_hop_partials_round_once_per_term(oracle, case, as_bf16):
+    y, w = _fma_case(case, as_bf16)
+    # both entries on one device: the partial row is the fused chain, the output adds it to +0
+    A = np.array([[0, 1]], dtype=np.int32)
+    same = oracle.plan(A, 2, 1)
+    h32, _, part = oracle.combine_two_hop_f32(same, y[same.slot_pair], w, want_partial=True)
+    assert float(part[0, 0]) == case["fused"] and float(h32[0, 0]) == case["fused"]
+    # one entry per device: each partial is one rounded product, and their sum has lost the last bit
+    split = oracle.plan(A, 2, 2)
+    h32, _, part = oracle.combine_two_hop_f32(split, y[split.slot_pair], w, want_partial=True)
+    assert float(part[split.pair_send_row[0], 0]) == case["y0"]
+    assert float(part[split.pair_send_row[1], 0]) == float(np.float32(case["w1"]) * np.float32(case["y1"]))
+    assert float(h32[0, 0]) == case["unfused"]
