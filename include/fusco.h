@@ -38,10 +38,12 @@ extern "C" {
 #define FUSCO_ERR_WORKSPACE (-2)   /* caller-provided memory too small                               */
 #define FUSCO_ERR_UNSUPPORTED (-3) /* dtype or flag combination not implemented                       */
 #define FUSCO_ERR_HIP (-4)         /* the HIP runtime refused a launch                                */
+#define FUSCO_ERR_STATIC_LIMIT (-5) /* fusco_plan_static: the input needs more scratch than the static buffer */
 
 #define FUSCO_MAX_K 64   /* experts per token                    */
 #define FUSCO_MAX_E 1024 /* experts (and therefore devices)      */
 #define FUSCO_MAX_ROW_BYTES (1u << 20) /* one row of the movers, both planes of a dispatch together */
+#define FUSCO_STATIC_SCRATCH_BYTES (4u << 20) /* planner scratch held by the library for fusco_plan_static */
 
 /* element types of fusco_combine */
 #define FUSCO_BF16 0
@@ -116,6 +118,23 @@ int fusco_layout_bind(fusco_layout *L, int32_t N, int32_t k, int32_t E, int32_t 
  * Every descriptor array is fully rewritten (send_src only in rows < U).  N == 0 is allowed.
  */
 int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size_t scratch_bytes, void *stream);
+
+/*
+ * fusco_plan for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments and results as fusco_plan,
+ * but the planner's scratch (per-tile and per-chunk counts) is a static array of FUSCO_STATIC_SCRATCH_BYTES
+ * (4 MiB) inside the library, present on every GPU the library runs on until the process ends.  The call
+ * allocates and frees nothing.  Inputs whose fusco_scratch_bytes() exceeds that size are refused with
+ * FUSCO_ERR_STATIC_LIMIT and nothing is launched (4 MiB covers about 7.9 million (token, expert) pairs at
+ * E + D = 264, e.g. 990 000 tokens with k = 8); use fusco_plan with a workspace of your own for those.
+ * The first call on a device looks up the address of that device's copy of the array (no allocation; make
+ * that first call outside a graph capture); the device current at the call must be the one `stream` belongs to.
+ * All calls on one GPU share the one array: two fusco_plan_static calls that may overlap on the same GPU
+ * (different streams, no ordering between them) race on it and give undefined descriptors; calls in one
+ * stream, or ordered by events, are safe.  The array needs no clearing: every call writes all counts it reads.
+ * Errors otherwise as fusco_plan; FUSCO_ERR_HIP also when the array's address cannot be resolved.
+ */
+int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
 
 /*
  * Fused gather-pack (section 3.2, intra-node path: descriptor interpretation inlined into the

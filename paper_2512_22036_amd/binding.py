@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -71,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_layout_bind.argtypes = [ctypes.POINTER(_CLayout), i32, i32, i32, i32, vp, sz]
     lib.fusco_plan.restype = ctypes.c_int
     lib.fusco_plan.argtypes = [ctypes.POINTER(_CLayout), vp, vp, sz, vp]
+    lib.fusco_plan_static.restype = ctypes.c_int
+    lib.fusco_plan_static.argtypes = [ctypes.POINTER(_CLayout), vp, vp]
     lib.fusco_dispatch.restype = ctypes.c_int
     lib.fusco_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, sz, vp, sz, vp, vp, vp, vp, u32, vp]
     lib.fusco_plan_dispatch.restype = ctypes.c_int
@@ -182,6 +184,15 @@ def fusco_plan(layout: Layout, topk_idx: torch.Tensor, stream=None) -> None:
         raise FuscoError("topk_idx must be a contiguous int32 device tensor of shape [N, k]")
     _check(load_library().fusco_plan(ctypes.byref(layout.c), topk_idx.data_ptr(), layout.scratch.data_ptr(),
                                      layout.scratch.numel(), _stream(stream)), "fusco_plan")
+
+
+def fusco_plan_static(layout: Layout, topk_idx: torch.Tensor, stream=None) -> None:
+    """fusco_plan on the library's own static scratch array: nothing is allocated or passed in."""
+    if (not topk_idx.is_cuda or topk_idx.dtype != torch.int32 or not topk_idx.is_contiguous()
+            or tuple(topk_idx.shape) != (layout.N, layout.k)):
+        raise FuscoError("topk_idx must be a contiguous int32 device tensor of shape [N, k]")
+    _check(load_library().fusco_plan_static(ctypes.byref(layout.c), topk_idx.data_ptr(), _stream(stream)),
+           "fusco_plan_static")
 
 
 def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.Tensor] = None,

@@ -11,6 +11,7 @@
 // One translation unit: the kernels live in the headers next to this file (planner.h, movers.h,
 // segments.h, probes.h), the host-side helpers in launch.h, the C entry points below.
 #include "launch.h"
+#include <mutex>
 
 extern "C" {
 
@@ -24,6 +25,7 @@ const char *fusco_status_string(int status)
     case FUSCO_ERR_WORKSPACE: return "caller-provided memory too small";
     case FUSCO_ERR_UNSUPPORTED: return "unsupported dtype or flags";
     case FUSCO_ERR_HIP: return "HIP launch failed";
+    case FUSCO_ERR_STATIC_LIMIT: return "input needs more planner scratch than the library's static buffer holds";
     default: return "unknown status";
     }
 }
@@ -133,6 +135,43 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
         else launch(plan_place_kernel<false, 2>, tiles, block, s, a, nullptr, ev.stop);
     }
     return launch_status();
+}
+
+// Planner scratch that belongs to the library, for fusco_plan_static.  In host code the array's name is
+// only a handle: the device address is looked up once per device with hipGetSymbolAddress and kept.
+static __device__ __align__(256) unsigned char g_static_scratch[FUSCO_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_static_scratch_ptr[kMaxDevices];   // per device: address of that GPU's copy of the array, or null
+std::mutex g_static_scratch_lock;
+
+// Device address of the calling thread's current GPU's copy of g_static_scratch, or null on failure.
+void *static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+    if (!g_static_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_static_scratch_ptr[dev] = p;
+    }
+    return g_static_scratch_ptr[dev];
+}
+}   // namespace
+
+int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream)
+{
+    if (!layout_ok(L) || (!d_topk_idx && L->N > 0)) return FUSCO_ERR_INVALID_ARG;
+    if (fusco_scratch_bytes(L->N, L->k, L->E, L->D) > FUSCO_STATIC_SCRATCH_BYTES) return FUSCO_ERR_STATIC_LIMIT;
+    void *scratch = static_scratch_of_current_device();
+    if (!scratch) return FUSCO_ERR_HIP;
+    // the planner writes every count it later reads, so the array needs no clearing between calls
+    return fusco_plan(L, d_topk_idx, scratch, FUSCO_STATIC_SCRATCH_BYTES, stream);
 }
 
 int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *d_x, size_t row_bytes,

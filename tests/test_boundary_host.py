@@ -107,6 +107,16 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_plan(None, buf, buf, scratch, None) == -1
     empty = _CLayout()
     assert lib.fusco_plan(ctypes.byref(empty), buf, buf, scratch, None) == -1
+    # plan on the library's static scratch: same checks, plus its size limit (refused before any device call)
+    assert lib.fusco_plan_static(ctypes.byref(L), None, None) == -1
+    assert lib.fusco_plan_static(None, buf, None) == -1
+    assert lib.fusco_plan_static(ctypes.byref(empty), buf, None) == -1
+    Lhuge = _CLayout()
+    huge = (1000000, 8, 256, 8)
+    assert lib.fusco_scratch_bytes(*huge) > (4 << 20) >= lib.fusco_scratch_bytes(990000, 8, 256, 8)
+    assert lib.fusco_layout_bind(ctypes.byref(Lhuge), *huge, base + (1 << 27), lib.fusco_layout_bytes(*huge)) == 0
+    assert lib.fusco_plan_static(ctypes.byref(Lhuge), buf, None) == -5
+    assert b"static" in lib.fusco_status_string(-5)
     # dispatch
     d = lambda *a: lib.fusco_dispatch(ctypes.byref(L), *a)
     assert d(None, 64, None, 0, buf, None, None, None, 0, None) == -1            # no x
