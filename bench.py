@@ -183,6 +183,51 @@ def measure_ceilings(fusco, torch, cfg, d_x, d_expert, d_out, reps):
     return out
 
 
+def write_study(fusco, torch, cfg, L, d_x, d_expert, reps):
+    """Where the write side of dispatch stands on this GPU: the expert tensor filled (and read) as 4 KiB pieces
+    with different assignments of pieces to the 8 XCDs, as whole rows, and by the dispatch itself.  Every fill
+    moves the same P * row_bytes bytes through the same address window; only which XCD writes which piece
+    changes.  Each variant is launched once to warm up and then `reps` times between two stream events, in the
+    order of the returned list (a profiler's per-dispatch rows follow the same order)."""
+    nbytes = cfg.P * cfg.row_bytes
+    flat = d_expert.view(torch.uint8).view(-1)
+    rows = d_expert.view(torch.uint8).view(cfg.P, -1)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pieces = nbytes // 4096
+    out = []
+
+    def timed(name, moved, fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        out.append({"variant": name, "us": us, "GBps": moved / (us * 1e-6) / 1e9, "launches": reps + 1})
+
+    if nbytes % 4096 == 0 and pieces % 8 == 0:
+        runs = [r for r in (1, 2, 4, 7, 8, 16, 32, 64, 256, pieces // 8) if (pieces // 8) % r == 0]
+        for r in runs:
+            timed("fill, 4 KiB pieces, runs of %d per XCD" % r, nbytes,
+                  lambda r=r: fusco.fusco_probe_pieces(flat, True, r))
+        timed("fill, 4 KiB pieces, scattered", nbytes, lambda: fusco.fusco_probe_pieces(flat, True, scatter=True))
+        for r in runs:
+            timed("read, 4 KiB pieces, runs of %d per XCD" % r, nbytes,
+                  lambda r=r: fusco.fusco_probe_pieces(flat, False, r, sink=sink))
+        timed("read, 4 KiB pieces, scattered", nbytes,
+              lambda: fusco.fusco_probe_pieces(flat, False, scatter=True, sink=sink))
+    timed("fill, whole rows in launch order", nbytes, lambda: fusco.fusco_probe_rows(None, rows, 0, 1, False))
+    timed("fill, whole rows scattered", nbytes, lambda: fusco.fusco_probe_rows(None, rows, 0, 1, True))
+    timed("read, whole rows in launch order", nbytes, lambda: fusco.fusco_probe_rows(rows, None, 1, 0, False, sink=sink))
+    timed("read, whole rows scattered", nbytes, lambda: fusco.fusco_probe_rows(rows, None, 1, 0, True, sink=sink))
+    timed("fusco_dispatch (reads N rows, writes P rows)", (cfg.N + cfg.P) * cfg.row_bytes,
+          lambda: fusco.fusco_dispatch(L, d_x, d_expert))
+    return {"workload": cfg.name, "row_bytes": cfg.row_bytes, "bytes_per_fill": nbytes, "reps": reps, "variants": out}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +245,9 @@ def main() -> int:
                     help="skip timing the two-hop dispatch and the disaggregated multi-stage baseline")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the plain row-traffic probes (fill, read, copy, 1:8 and 8:1 mixes) of the same sizes")
+    ap.add_argument("--write-study", action="store_true",
+                    help="instead of the benchmark line, print the write-side study: fills and reads of the expert "
+                         "tensor with different assignments of 4 KiB pieces to the XCDs, whole rows, the dispatch")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -261,6 +309,13 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+
+    if args.write_study:
+        if cfg.payload != "bf16":
+            print("bench.py: --write-study needs a bf16 configuration", file=sys.stderr)
+            return 2
+        print(json.dumps({"write_study": write_study(fusco, torch, cfg, L, d_x, d_expert, max(3, args.steps // 10))}))
+        return 0
 
     run_step = step
     if args.graph and len(sets) > 1:

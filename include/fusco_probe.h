@@ -39,6 +39,36 @@ int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t
                      uint32_t *d_sink, void *stream);
 
 /*
+ * Measurement aid: d_buf (bytes a multiple of 4096, 16-byte aligned) written (write != 0) or read as a stream
+ * of 4 KiB pieces, one workgroup per piece, one 16-byte access per thread, with a chosen assignment of pieces
+ * to the 8 XCDs of the GPU.  The hardware hands workgroups to the XCDs in turn, so workgroup b = 8 i + x runs on
+ * XCD x; it takes piece ((i / run) * 8 + x) * run + i mod run, i.e. every XCD works through runs of run_pieces
+ * consecutive pieces and the 8 runs of a round lie next to each other.  The bytes moved, and the address window
+ * in flight across the chip, are the same for every run_pieces; only which XCD touches which piece changes.
+ * run_pieces == 1 is plain launch order; pieces / 8 gives each XCD one contiguous eighth of the buffer.
+ * Requires pieces % 8 == 0 and (pieces / 8) % run_pieces == 0.  scatter != 0 ignores run_pieces and sends
+ * workgroup b to piece b * m mod pieces, m coprime to the piece count.  A written piece holds its own index in
+ * word 0 of each 16-byte unit.  d_sink (one uint32 on the device) is needed for reads and never written in
+ * practice.
+ */
+int fusco_probe_pieces(void *d_buf, size_t bytes, int write, uint32_t run_pieces, int scatter, uint32_t *d_sink,
+                       void *stream);
+
+/*
+ * Validation aid: the consumer side of the slice protocol of fusco_segments_copy (the role a network engine
+ * plays in the paper's pipelined workflow, section 3.2: it takes a slice as soon as the slice is ready).  One
+ * workgroup, meant to run on another stream while fusco_segments_copy packs d_stream: it walks the
+ * ceil(total_bytes / slice_bytes) slices in order, polls d_slice_fill[s] with acquire loads at system scope
+ * until the count reaches the slice's size, and then adds up the slice's 32-bit words.  The kernel always
+ * ends: it polls at most max_polls times in all (at most 2^24), after which the remaining slices are
+ * reported as not ready.  d_report: [slices][4] uint32 = { seen complete (0/1), polls spent waiting for it, low
+ * and high 32 bits of the 64-bit sum of the slice's 32-bit words }.  total_bytes must be the exact size of the
+ * packed stream (a multiple of 16).  The caller zeroes d_slice_fill before launching the two sides.
+ */
+int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint64_t slice_bytes,
+                               const uint32_t *d_slice_fill, uint32_t max_polls, uint32_t *d_report, void *stream);
+
+/*
  * Measurement aid: kernel time without stream events between the kernels.  The next fusco_plan,
  * fusco_dispatch (fused modes), fusco_plan_dispatch or fusco_combine call made by the calling thread attaches the two HIP
  * events (hipEvent_t passed as void*, created with timing enabled) to its own kernels: start_event

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_time_next_call",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -86,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_rows.restype = ctypes.c_int
     lib.fusco_probe_rows.argtypes = [vp, u32, vp, u32, sz, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                      vp, vp]
+    lib.fusco_probe_pieces.restype = ctypes.c_int
+    lib.fusco_probe_pieces.argtypes = [vp, sz, ctypes.c_int, u32, ctypes.c_int, vp, vp]
+    lib.fusco_probe_consume_slices.restype = ctypes.c_int
+    lib.fusco_probe_consume_slices.argtypes = [vp, ctypes.c_uint64, ctypes.c_uint64, vp, u32, vp, vp]
     lp = ctypes.POINTER(_CLayout)
     u64, i64 = ctypes.c_uint64, ctypes.c_int64
     lib.fusco_segments_scan.restype = ctypes.c_int
@@ -395,6 +399,33 @@ def fusco_probe_rows(src, dst, reads: int, writes: int, scatter: bool, write_thr
     _check(load_library().fusco_probe_rows(_ptr(src), rows[0], _ptr(dst), rows[1], row_bytes, int(reads), int(writes),
                                            int(bool(scatter)), int(bool(write_through)), _ptr(sink), _stream(stream)),
            "fusco_probe_rows")
+
+
+def fusco_probe_pieces(buf: torch.Tensor, write: bool, run_pieces: int = 1, scatter: bool = False,
+                       sink: torch.Tensor | None = None, stream=None) -> None:
+    """buf: contiguous device tensor whose size is a multiple of 4096 bytes; see fusco_probe.h."""
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise FuscoError("probe pieces needs a contiguous device tensor")
+    if sink is not None and (not sink.is_cuda or sink.numel() < 1 or sink.element_size() != 4):
+        raise FuscoError("sink must be one 32-bit word on the device")
+    _check(load_library().fusco_probe_pieces(buf.data_ptr(), buf.numel() * buf.element_size(), int(bool(write)),
+                                             int(run_pieces), int(bool(scatter)), _ptr(sink), _stream(stream)),
+           "fusco_probe_pieces")
+
+
+def fusco_probe_consume_slices(packed: torch.Tensor, total_bytes: int, slice_bytes: int, slice_fill: torch.Tensor,
+                               max_polls: int, report: torch.Tensor, stream=None) -> None:
+    """report: int32 [slices, 4] on the device (ready, polls, checksum low, checksum high per slice)."""
+    slices = (total_bytes + slice_bytes - 1) // slice_bytes if slice_bytes > 0 else 0
+    if not packed.is_cuda or not packed.is_contiguous() or packed.numel() * packed.element_size() < total_bytes:
+        raise FuscoError("packed must be a contiguous device tensor of at least total_bytes")
+    if not slice_fill.is_cuda or slice_fill.dtype != torch.int32 or slice_fill.numel() < slices:
+        raise FuscoError("slice_fill must be an int32 device tensor with one entry per slice")
+    if not report.is_cuda or report.dtype != torch.int32 or not report.is_contiguous() or report.numel() < 4 * slices:
+        raise FuscoError("report must be a contiguous int32 device tensor of shape [slices, 4]")
+    _check(load_library().fusco_probe_consume_slices(packed.data_ptr(), total_bytes, slice_bytes, slice_fill.data_ptr(),
+                                                     max_polls, report.data_ptr(), _stream(stream)),
+           "fusco_probe_consume_slices")
 
 
 def fusco_disaggregated_plan(rank_layout: Layout, layout: Layout, topk_idx: torch.Tensor, topk_dev: torch.Tensor,

@@ -310,6 +310,7 @@ int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, c
     a.k = L->k;
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
     a.pair_send_row = L->pair_send_row; a.send_src = L->send_src; a.n_rows_dev = L->send_off + L->D;
+    a.first = 0;
     int threads = round_up(a.C, kWave);
     if (threads > 1024) threads = 1024;
     const dim3 grid((unsigned)L->send_cap, (unsigned)((a.C + threads - 1) / threads));
@@ -499,6 +500,41 @@ int fusco_probe_rows(const void *d_src, uint32_t src_rows, void *d_dst, uint32_t
     else if (R == 1 && W == 1) hipLaunchKernelGGL((probe_rows_kernel<1, 1>), grid, block, 0, s, a);
     else if (R == 1) hipLaunchKernelGGL((probe_rows_kernel<1, 8>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((probe_rows_kernel<8, 1>), grid, block, 0, s, a);
+    return launch_status();
+}
+
+int fusco_probe_pieces(void *d_buf, size_t bytes, int write, uint32_t run_pieces, int scatter, uint32_t *d_sink,
+                       void *stream)
+{
+    if (!d_buf || !aligned16(d_buf) || bytes == 0 || bytes % 4096 != 0 || bytes / 4096 > 0x7FFFFFFFu)
+        return FUSCO_ERR_INVALID_ARG;
+    const uint32_t pieces = (uint32_t)(bytes / 4096);
+    if (scatter ? pieces < 3 : (run_pieces == 0 || pieces % 8u != 0 || (pieces / 8u) % run_pieces != 0))
+        return FUSCO_ERR_INVALID_ARG;
+    if (!write && !d_sink) return FUSCO_ERR_INVALID_ARG;
+    ProbePiecesArgs a;
+    a.buf = (u32x4 *)d_buf; a.sink = d_sink; a.pieces = pieces;
+    a.run = scatter ? 1u : run_pieces;
+    a.mul = scatter ? coprime_near(pieces, 0.6180339887498949) : 0u;
+    hipStream_t s = (hipStream_t)stream;
+    if (write) hipLaunchKernelGGL(probe_pieces_kernel<true>, dim3(pieces), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(probe_pieces_kernel<false>, dim3(pieces), dim3(256), 0, s, a);
+    return launch_status();
+}
+
+int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint64_t slice_bytes,
+                               const uint32_t *d_slice_fill, uint32_t max_polls, uint32_t *d_report, void *stream)
+{
+    if (!d_stream || !aligned16(d_stream) || !d_slice_fill || !d_report) return FUSCO_ERR_INVALID_ARG;
+    if (slice_bytes == 0 || slice_bytes % 16 != 0 || slice_bytes > ((uint64_t)1 << 31) || total_bytes % 16 != 0)
+        return FUSCO_ERR_INVALID_ARG;
+    const uint64_t slices = (total_bytes + slice_bytes - 1) / slice_bytes;
+    if (slices > (1u << 20) || max_polls > (1u << 24)) return FUSCO_ERR_INVALID_ARG;
+    if (slices == 0) return FUSCO_OK;
+    ConsumeArgs a;
+    a.stream = (const u32x4 *)d_stream; a.slice_fill = d_slice_fill; a.total = total_bytes; a.slice_bytes = slice_bytes;
+    a.n_slices = (uint32_t)slices; a.max_polls = max_polls; a.report = d_report;
+    hipLaunchKernelGGL(consume_slices_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, a);
     return launch_status();
 }
 

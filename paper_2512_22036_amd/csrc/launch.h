@@ -103,6 +103,20 @@ int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_
     return FUSCO_OK;
 }
 
+// Where the combine walk starts.  Right after a dispatch of the same tokens the memory-side cache (256 MB)
+// still holds the rows written for the last tokens.  Measured on MI355X (8192 tokens x 8 rows of 14 KiB): a
+// walk that starts about 110-220 MiB of rows before the end, goes up to the last token and then wraps to
+// token 0 is 7 us (2 %) faster than a walk from the last token down, and 25 us faster than one from token 0
+// up.  When y comes from somewhere else the order makes no difference.
+constexpr size_t kRecentRowBytes = (size_t)160 << 20;
+
+int combine_first_row(int N, int k, size_t row_bytes)
+{
+    const size_t per_token = (size_t)k * row_bytes;
+    const size_t recent = kRecentRowBytes / (per_token ? per_token : 1);
+    return recent >= (size_t)N ? 0 : N - (int)recent;
+}
+
 // out[t] = sum_j w[t, j] * y[pair_slot[t * k + j]] for N tokens; arguments already checked
 void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int y_dtype, const float *d_w,
                     void *d_out, int out_dtype, int32_t H, hipStream_t s, hipEvent_t e0 = nullptr,
@@ -116,6 +130,7 @@ void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int
     a.k = k;
     a.pair_send_row = nullptr; a.send_src = nullptr; a.n_rows_dev = nullptr;
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
+    a.first = combine_first_row(N, k, (size_t)a.C * 16);
     // one workgroup per token whenever the row fits 1024 threads
     int threads = round_up(a.C, kWave);
     if (threads > 1024) threads = 1024;

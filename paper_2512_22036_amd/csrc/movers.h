@@ -150,6 +150,7 @@ struct CombineArgs {
     const int32_t *pair_slot;
     int32_t k;
     int32_t C;   // 16-byte chunks per y row
+    int32_t first;   // row handled by workgroup 0; the walk goes upwards from there and wraps around
     // per-send-row mode (level 2 reversed): one workgroup per send row, only the token's entries on that row
     const int32_t *pair_send_row, *send_src, *n_rows_dev;
 };
@@ -169,9 +170,11 @@ template <bool Y_BF16, bool OUT_BF16, int CPT, int JU, bool PER_SEND_ROW = false
 __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
 {
     constexpr int EPC = Y_BF16 ? 8 : 4;   // elements per 16-byte chunk of y
-    // last row first: when combine follows dispatch, the rows written last are the ones still in
-    // the memory-side cache
-    const int r = gridDim.x - 1 - blockIdx.x;   // token, or send row in the per-send-row mode
+    // The walk starts at row a.first and wraps: when combine follows dispatch, the rows of the last
+    // tokens are still in the memory-side cache, and reading them first, oldest first, finds them
+    // there before the walk's own traffic pushes them out (see combine_first_row).
+    int r = a.first + (int)blockIdx.x;   // token, or send row in the per-send-row mode
+    if (r >= (int)gridDim.x) r -= (int)gridDim.x;
     int t = r;
     if constexpr (PER_SEND_ROW) {
         if (r >= *a.n_rows_dev) return;

@@ -224,6 +224,16 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_copy(buf, buf + 4096, 24, None) == -1
     assert lib.fusco_probe_copy(buf, buf + 4096, 0, None) == 0
     assert lib.fusco_probe_time_next_call(None, buf) == -1 and lib.fusco_probe_time_next_call(buf, None) == -1
+    # probe pieces
+    pp = lib.fusco_probe_pieces
+    assert pp(None, 1 << 20, 1, 1, 0, None, None) == -1
+    assert pp(buf, (1 << 20) + 16, 1, 1, 0, None, None) == -1              # not whole pieces
+    assert pp(buf, 4096 * 12, 1, 1, 0, None, None) == -1                   # pieces not a multiple of 8
+    assert pp(buf, 4096 * 64, 1, 3, 0, None, None) == -1                   # 8 pieces per XCD do not split into runs of 3
+    assert pp(buf, 4096 * 64, 1, 0, 0, None, None) == -1
+    assert pp(buf, 4096 * 64, 0, 1, 0, None, None) == -1                   # reads need the sink
+    assert pp(buf + 8, 4096 * 64, 1, 1, 0, None, None) == -1
+    assert pp(buf, 4096 * 2, 1, 1, 1, None, None) == -1                    # too few pieces to scatter
     # probe rows: unsupported shapes, bad sizes, missing buffers (nothing is launched on error)
     pr = lib.fusco_probe_rows
     assert pr(buf, 8, buf + 4096, 8, 64, 2, 1, 0, 0, None, None) == -1        # shape not offered

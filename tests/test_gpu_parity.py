@@ -104,41 +104,66 @@ def _random_shape(rng):
 
 
 def test_random_shapes_whole_path(fusco, oracle):
-    """300 random shapes (sizes, k, E, D, repeated or distinct experts, tile-boundary token counts): plan,
-    dispatch (expert and wire tensors) and combine against the oracle, element by element."""
+    """300 random shapes (sizes, k, E, D, repeated or distinct experts, tile-boundary token counts, rows from 16
+    bytes to 18 KiB so that every chunks-per-thread variant of the movers is drawn, an optional second plane):
+    plan, dispatch (expert and wire tensors, both planes) and combine against the oracle, element by element."""
     rng = np.random.default_rng(20251127)
+    seen_chunks = set()
     for case in range(300):
         N, k, E, D, distinct = _random_shape(rng)
-        C = int(rng.choice([1, 2, 5, 16, 33, 64]))             # 16-byte units per row
+        # 16-byte units per row: up to 64 for any shape, up to 1152 (18 KiB) where the expert tensor stays small
+        budget = max(1, (48 << 20) // (16 * N * k))
+        C = int(rng.choice([1, 2, 5, 16, 33, 64, 127, 128, 200, 511, 512, 896, 1152]))
+        C = min(C, budget) if C > 64 else C
+        Ca = int(rng.choice([0, 0, 1, 3, 14])) if C + 14 <= max(budget, 64) else 0      # second plane, 16-byte units
+        seen_chunks.add(4 if C + Ca >= 512 else (2 if C + Ca >= 128 else 1))
         A = random_topk(rng, N, k, E, distinct)
         want = oracle.plan(A, E, D)
         L, got = gpu_plan(fusco, A, E, D)
-        tag = "case %d: N=%d k=%d E=%d D=%d distinct=%s C=%d" % (case, N, k, E, D, distinct, C)
+        tag = "case %d: N=%d k=%d E=%d D=%d distinct=%s C=%d Ca=%d" % (case, N, k, E, D, distinct, C, Ca)
         for f in PLAN_FIELDS:
             assert np.array_equal(getattr(got, f), getattr(want, f)), (tag, f)
         H = C * 8
         xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
-        send_want, expert_want = oracle.dispatch(want, xb)
         eb = torch.zeros((L.P, H), dtype=torch.bfloat16, device="cuda")
         sb = torch.zeros((L.send_cap, H), dtype=torch.bfloat16, device="cuda")
-        fusco.fusco_dispatch(L, bf16_dev(xb), eb, send_buf=sb, flags=3)
+        if Ca:
+            xa = rng.integers(0, 2 ** 32, size=(N, Ca * 4), dtype=np.uint32)
+            send_want, expert_want, send_aux_want, expert_aux_want = oracle.dispatch(want, xb, xa)
+            ea = torch.zeros((L.P, Ca * 4), dtype=torch.int32, device="cuda")
+            sa = torch.zeros((L.send_cap, Ca * 4), dtype=torch.int32, device="cuda")
+            fusco.fusco_dispatch(L, bf16_dev(xb), eb, x_aux=dev(xa.view(np.int32)), expert_aux=ea, send_buf=sb,
+                                 send_aux=sa, flags=3)
+        else:
+            send_want, expert_want = oracle.dispatch(want, xb)
+            fusco.fusco_dispatch(L, bf16_dev(xb), eb, send_buf=sb, flags=3)
         w = rng.random((N, k)).astype(np.float32)
         out = torch.zeros((N, H), dtype=torch.bfloat16, device="cuda")
         fusco.fusco_combine(L, eb, dev(w), out)
         torch.cuda.synchronize()
         assert np.array_equal(bits_host(eb), expert_want), tag
         assert np.array_equal(bits_host(sb[:want.U]), send_want), tag
+        if Ca:
+            assert np.array_equal(ea.cpu().numpy().view(np.uint32), expert_aux_want), tag
+            assert np.array_equal(sa[:want.U].cpu().numpy().view(np.uint32), send_aux_want), tag
         _, o16 = oracle.combine_f32(expert_want, w, want.pair_slot)
         assert np.array_equal(bits_host(out), o16), tag
         if N <= 2048 // k:                                      # the single-launch path gives the same
             L2 = fusco.Layout(N, k, E, D)
             eb2 = torch.zeros_like(eb)
-            fusco.fusco_plan_dispatch(L2, dev(A), bf16_dev(xb), eb2)
+            if Ca:
+                ea2 = torch.zeros_like(ea)
+                fusco.fusco_plan_dispatch(L2, dev(A), bf16_dev(xb), eb2, x_aux=dev(xa.view(np.int32)), expert_aux=ea2)
+            else:
+                fusco.fusco_plan_dispatch(L2, dev(A), bf16_dev(xb), eb2)
             torch.cuda.synchronize()
             got2 = L2.to_host()
             for f in PLAN_FIELDS:
                 assert np.array_equal(getattr(got2, f), getattr(want, f)), (tag, "fused", f)
             assert torch.equal(eb2, eb), tag
+            if Ca:
+                assert torch.equal(ea2, ea), tag
+    assert seen_chunks == {1, 2, 4}          # one, two and four 16-byte chunks per thread were all exercised
 
 
 def test_plan_empty_input(fusco, oracle):

@@ -130,3 +130,29 @@ def test_call_timing_events(fusco):
         assert 0.0005 < ms < 5.0, (i, ms)
     # the calls ran in stream order: plan ends before dispatch starts, dispatch before combine
     assert ev[1].elapsed_time(ev[2]) >= 0.0 and ev[3].elapsed_time(ev[4]) >= 0.0
+
+
+@pytest.mark.parametrize("pieces,run", [(8, 1), (64, 1), (64, 2), (64, 8), (56, 7), (4096, 16), (4096, 512), (229376, 7)])
+def test_pieces_probe_writes_every_piece_exactly_once(fusco, pieces, run):
+    buf = torch.full((pieces, 1024), -1, dtype=torch.int32, device="cuda")          # 4 KiB per row
+    fusco.fusco_probe_pieces(buf, write=True, run_pieces=run)
+    got = buf.cpu().numpy().view(np.uint32).reshape(pieces, 256, 4)
+    assert np.array_equal(got[:, :, 0], np.repeat(np.arange(pieces, dtype=np.uint32)[:, None], 256, axis=1))
+    assert np.array_equal(got[:, :, 1], np.repeat(np.arange(256, dtype=np.uint32)[None, :], pieces, axis=0))
+    # the workgroup that wrote piece p: XCD (b mod 8) owns runs of `run` pieces, 8 runs to a round
+    b = got[:, 0, 2].astype(np.int64)
+    p = np.arange(pieces)
+    assert np.array_equal(np.sort(b), p)
+    assert np.array_equal(b % 8, (p // run) % 8)
+    # scattered: still every piece once; reads touch nothing
+    buf.fill_(-1)
+    fusco.fusco_probe_pieces(buf, write=True, scatter=True)
+    got = buf.cpu().numpy().view(np.uint32).reshape(pieces, 256, 4)
+    assert np.array_equal(got[:, 0, 0], np.arange(pieces, dtype=np.uint32))
+    assert np.array_equal(np.sort(got[:, 0, 2]), np.arange(pieces, dtype=np.uint32))
+    before = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    fusco.fusco_probe_pieces(buf, write=False, run_pieces=run, sink=sink)
+    fusco.fusco_probe_pieces(buf, write=False, scatter=True, sink=sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before) and int(sink.item()) == 0

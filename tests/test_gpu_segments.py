@@ -143,3 +143,53 @@ def test_offsets_that_wrap_are_counted_and_touch_nothing(fusco):
     assert np.array_equal(dst.cpu().numpy(), want)
     assert bool((out_room[0] == 0xEE).all()) and bool((out_room[2] == 0xEE).all()) and bool((out_room[1, 256:] == 0xEE).all())
     assert bool((room[0] == 0x5A).all()) and bool((room[2] == 0x5A).all())
+
+
+def test_consumer_on_another_stream_sees_complete_slices_only(fusco, oracle):
+    """The slice protocol under concurrency (section 3.2, pipelined workflow: the consumer takes a slice as soon
+    as it is ready).  A consumer workgroup on a second stream polls the per-slice byte counters while
+    fusco_segments_copy packs the stream, and adds up the words of every slice it sees complete: each such sum
+    must be the sum of that slice of the oracle's packed stream, i.e. a complete counter implies visible bytes.
+    The consumer's polling is bounded, so the test ends whatever the scheduling."""
+    rng = np.random.default_rng(99)
+    n = 12000
+    size, off, span = _random_layout(rng, n, max_units=1200)      # segments of 16 B .. 19 KB, about 115 MB in all
+    src = rng.integers(0, 256, size=span, dtype=np.uint8)
+    slice_bytes = 1 << 20
+    want, fill_want = oracle.segments_copy(src, size, src_off=off, slice_bytes=slice_bytes)
+    total = int(size.sum())
+    slices = len(fill_want)
+    words = np.zeros(slices * (slice_bytes // 4), dtype=np.uint32)
+    words[:total // 4] = want.view(np.uint32)
+    sums_want = words.reshape(slices, -1).astype(np.uint64).sum(axis=1)
+
+    d_src, d_desc = dev(src), desc_dev(off, size)
+    cum, status = scan(fusco, d_desc)
+    produce, consume = torch.cuda.Stream(), torch.cuda.Stream()
+    waited_total = 0
+    for attempt in range(3):
+        packed = torch.zeros(total + 4096, dtype=torch.uint8, device="cuda")
+        fill = torch.zeros(slices, dtype=torch.int32, device="cuda")
+        report = torch.full((slices, 4), -1, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(consume):
+            fusco.fusco_probe_consume_slices(packed, total, slice_bytes, fill, 1 << 20, report)
+        with torch.cuda.stream(produce):
+            fusco.fusco_segments_copy(d_src, d_desc, packed, None, cum, total + 4096, status, slice_bytes=slice_bytes,
+                                      slice_fill=fill)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        assert np.array_equal(fill.cpu().numpy().astype(np.uint32), fill_want)
+        assert np.array_equal(packed[:total].cpu().numpy(), want)
+        rep = report.cpu().numpy().view(np.uint32).astype(np.uint64)
+        ready, polls = rep[:, 0], rep[:, 1]
+        sums = rep[:, 2] | (rep[:, 3] << np.uint64(32))
+        assert set(ready.tolist()) <= {0, 1}
+        # the one thing the protocol promises: a slice seen complete had all its bytes visible
+        assert np.array_equal(sums[ready == 1], sums_want[ready == 1]), attempt
+        # the consumer's poll budget is far beyond the producer's run time, so it sees every slice
+        assert int(ready.sum()) == slices, (attempt, int(ready.sum()), slices)
+        waited_total += int((polls > 0).sum())
+        print("attempt %d: consumer had to wait for %d of %d slices" % (attempt, int((polls > 0).sum()), slices), flush=True)
+    # over three runs the consumer was at least once ahead of the producer (it starts first): the two did overlap
+    assert waited_total > 0
