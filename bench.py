@@ -23,12 +23,27 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
-# HBM-side traffic per launch in bytes, from the rocprofv3 --pmc runs summarised in
-# profiles/bench_dsv3_hbm_traffic_pmc.txt: FETCH_SIZE and WRITE_SIZE per dispatch, each scaled by what
-# the same counter reads for the 1 GiB plain-copy probe (1.99994 and 1.00000 KiB per count).
-MEASURED_TRAFFIC_BYTES = {
-    "dsv3": {"dispatch": 119459533 + 939524096, "combine": 941655877 + 117440512},
-}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_dsv3_hbm_traffic_pmc.txt")
+
+
+def measured_traffic(workload: str):
+    """HBM-side bytes per launch of the two movers, read from the tracked rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE and WRITE_SIZE per dispatch, scaled there by what the same counters read for a plain
+    1 GiB copy).  The counters need the profiler, so they cannot be taken inside a timed run; the summary names
+    the library source it was taken with, and tests/test_profiles.py fails when that differs from the tree.
+    Returns {"dispatch": bytes, "combine": bytes} or {} when there is no summary for the workload."""
+    out = {}
+    try:
+        lines = open(TRAFFIC_PROFILE).read().splitlines()
+    except OSError:
+        return out
+    if not any(l.startswith("workload:") and l.split(":", 1)[1].strip() == workload for l in lines):
+        return out
+    for l in lines:
+        f = l.split()
+        if len(f) >= 5 and f[0] in ("dispatch_kernel", "combine_kernel"):
+            out[f[0].split("_")[0]] = int(f[3]) + int(f[4])          # read bytes + written bytes
+    return out
 
 
 def cpu_baseline(cfg, total_tokens, A, w, xb, min_seconds=8.0, max_passes=64):
@@ -228,6 +243,66 @@ def write_study(fusco, torch, cfg, L, d_x, d_expert, reps):
     return {"workload": cfg.name, "row_bytes": cfg.row_bytes, "bytes_per_fill": nbytes, "reps": reps, "variants": out}
 
 
+def cache_probe(fusco, torch, row_bytes, reps=5):
+    """Reading a buffer that is cold, that has just been read, and that has just been written: what the 256 MB
+    memory-side cache does to a read that follows a write of the same rows (combine after dispatch).  2 GiB are
+    written between the measurements so that every one starts from the same state.  Median of `reps`."""
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    scrub = torch.empty((2 << 30) // 16384, 16384, dtype=torch.uint8, device="cuda")
+
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3
+
+    out = []
+    for mb in (64, 128, 192, 256, 384, 512, 940):
+        rows = mb * (1 << 20) // row_bytes
+        buf = torch.empty((rows, row_bytes), dtype=torch.uint8, device="cuda")
+        read = lambda: fusco.fusco_probe_rows(buf, None, 1, 0, False, sink=sink)
+        res = {"MB": mb, "bytes": rows * row_bytes}
+        for mode, before in (("cold", None), ("after_read", read),
+                             ("after_fill", lambda: fusco.fusco_probe_rows(None, buf, 0, 1, False)),
+                             ("after_write_through_fill", lambda: fusco.fusco_probe_rows(None, buf, 0, 1, False, True))):
+            ts = []
+            for _ in range(reps):
+                fusco.fusco_probe_rows(None, scrub, 0, 1, False)
+                torch.cuda.synchronize()
+                if before is not None:
+                    before()
+                ts.append(timed(read))
+            ts.sort()
+            res[mode + "_us"] = ts[len(ts) // 2]
+        out.append(res)
+        del buf
+    return {"row_bytes": row_bytes, "reps": reps, "sizes": out}
+
+
+def plan_scaling(fusco, torch, reps=20):
+    """fusco_plan alone over growing inputs (k = 8, E = 256, D = 8, uniform random experts): event-timed mean."""
+    out = []
+    for N in (8192, 32768, 131072, 524288, 2097152):
+        k, E, D = 8, 256, 8
+        rng = np.random.default_rng(N)
+        d_A = torch.from_numpy(rng.integers(0, E, size=(N, k), dtype=np.int32)).cuda()
+        L = fusco.Layout(N, k, E, D)
+        fusco.fusco_plan(L, d_A)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fusco.fusco_plan(L, d_A)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        out.append({"N": N, "pairs": N * k, "plan_us": us, "ns_per_pair": us * 1e3 / (N * k)})
+        del L, d_A
+    return {"k": 8, "E": 256, "D": 8, "reps": reps, "sizes": out}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -248,6 +323,11 @@ def main() -> int:
     ap.add_argument("--write-study", action="store_true",
                     help="instead of the benchmark line, print the write-side study: fills and reads of the expert "
                          "tensor with different assignments of 4 KiB pieces to the XCDs, whole rows, the dispatch")
+    ap.add_argument("--cache-probe", action="store_true",
+                    help="instead of the benchmark line, print the memory-side cache probe: a buffer read cold, "
+                         "right after a read and right after a write of it")
+    ap.add_argument("--plan-scaling", action="store_true",
+                    help="instead of the benchmark line, print fusco_plan's time for 8 Ki to 2 Mi tokens")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -268,6 +348,12 @@ def main() -> int:
     torch.cuda.set_device(0)
 
     cfg = W.get_config(args.config)
+    if args.cache_probe:
+        print(json.dumps({"cache_probe": cache_probe(fusco, torch, cfg.row_bytes)}))
+        return 0
+    if args.plan_scaling:
+        print(json.dumps({"plan_scaling": plan_scaling(fusco, torch)}))
+        return 0
     A, w = W.make_routing(cfg)
     d_A = torch.from_numpy(A).cuda()
     d_w = torch.from_numpy(w).cuda()
@@ -375,6 +461,52 @@ def main() -> int:
     ms = np.array([[ev[i][2 * j].elapsed_time(ev[i][2 * j + 1]) for j in range(3)] for i in range(K)])   # [K, 3]
     plan_ms, disp_ms, comb_ms = ms.mean(axis=0)
 
+    # the same step with the experts' output in a buffer of its own (an expert computation sits between dispatch
+    # and combine in an MoE layer, section 2.1): combine then finds none of its rows in the memory-side cache, and
+    # dispatch's freshly written rows are pushed out of it while combine runs
+    own_y = None
+    if cfg.payload == "bf16" and len(sets) == 1 and not args.graph:
+        d_y2 = d_expert.clone()
+        K2 = max(20, K // 4)
+        nbytes2 = 2 * (cfg.N + cfg.P) * cfg.row_bytes
+
+        def own_buffer_step(dispatch_flags):
+            def step2():
+                fusco.fusco_plan(L, d_A)
+                fusco.fusco_dispatch(L, d_x, d_expert, flags=dispatch_flags)
+                fusco.fusco_combine(L, d_y2, d_w, d_out)
+            for _ in range(5):
+                step2()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(K2):
+                step2()
+            torch.cuda.synchronize()
+            wall2 = time.perf_counter() - t0
+            ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K2)]
+            for row in ev2:
+                for e in row:
+                    e.record()
+            torch.cuda.synchronize()
+            for i in range(K2):
+                fusco.fusco_plan(L, d_A)
+                fusco.fusco_probe_time_next_call(ev2[i][0], ev2[i][1])
+                fusco.fusco_dispatch(L, d_x, d_expert, flags=dispatch_flags)
+                fusco.fusco_probe_time_next_call(ev2[i][2], ev2[i][3])
+                fusco.fusco_combine(L, d_y2, d_w, d_out)
+            torch.cuda.synchronize()
+            d2 = float(np.mean([ev2[i][0].elapsed_time(ev2[i][1]) for i in range(K2)]))
+            c2 = float(np.mean([ev2[i][2].elapsed_time(ev2[i][3]) for i in range(K2)]))
+            return {"steps": K2, "ms_per_step": wall2 * 1e3 / K2, "tokens_per_s": cfg.N * K2 / wall2,
+                    "dispatch_ms": d2, "combine_ms": c2,
+                    "dispatch_plus_combine": {"ms": d2 + c2, "GBps": nbytes2 / ((d2 + c2) * 1e-3) / 1e9,
+                                              "frac_of_peak": nbytes2 / ((d2 + c2) * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+        own_y = {"plain_dispatch": own_buffer_step(0),
+                 "streaming_dispatch": own_buffer_step(fusco.DISPATCH_STREAMING)}
+        del d_y2
+        step()                       # leave the buffers as the headline step leaves them
+        torch.cuda.synchronize()
+
     variants = None
     if not args.no_variants and cfg.payload == "bf16":
         variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
@@ -433,7 +565,10 @@ def main() -> int:
         del src, dst
 
     # sanity: the identity-expert round trip gives sum_j w_j * x[t] = x[t] up to rounding
-    err = (d_out[:64].float() - d_x[:64].float()).abs().max().item() if cfg.payload == "bf16" else 0.0
+    err = 0.0
+    if cfg.payload == "bf16":
+        for r0 in range(0, cfg.N, 4096):
+            err = max(err, (d_out[r0:r0 + 4096].float() - d_x[r0:r0 + 4096].float()).abs().max().item())
     if not err < 0.05:
         print("bench.py: round trip is wrong (max error %g)" % err, file=sys.stderr)
         return 1
@@ -475,7 +610,8 @@ def main() -> int:
                    "N": cfg.N, "hidden": cfg.H, "E": cfg.E, "k": cfg.k, "D": cfg.D, "seed": cfg.seed},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(dom),
+                     "traffic": measured_traffic(cfg.name).get(dom),
+                     "traffic_source": "profiles/bench_dsv3_hbm_traffic_pmc.txt (rocprofv3 --pmc run of this bench)",
                      "timing": "mean over a second pass of the same K steps; each call's kernels record their own "
                                "start and end HIP events (no stream events between kernels)"},
         "kernels": kernels,
@@ -485,6 +621,8 @@ def main() -> int:
         "launch": "one HIP graph replay per step" if args.graph else "three library calls per step",
         "buffer_sets": len(sets),
     }
+    if own_y is not None:
+        result["expert_output_in_own_buffer"] = own_y
     if fused is not None:
         result["fused_plan_dispatch_step"] = fused
     if ceilings is not None:

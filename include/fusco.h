@@ -31,7 +31,7 @@
 extern "C" {
 #endif
 
-#define FUSCO_VERSION 100
+#define FUSCO_VERSION 110
 
 #define FUSCO_OK 0
 #define FUSCO_ERR_INVALID_ARG (-1) /* null pointer, size out of range, misaligned pointer or row size */
@@ -49,10 +49,11 @@ extern "C" {
 #define FUSCO_BF16 0
 #define FUSCO_F32 1
 
-/* flags of fusco_dispatch (0 means FUSCO_DISPATCH_EXPERT) */
+/* flags of fusco_dispatch (no tensor flag means FUSCO_DISPATCH_EXPERT) */
 #define FUSCO_DISPATCH_EXPERT 1u /* write the expert-activation tensor (level 2 result)       */
 #define FUSCO_DISPATCH_WIRE 2u   /* write the deduplicated per-device receive tensors (level 1) */
 #define FUSCO_DISPATCH_TWO_HOP 4u /* hop by hop: x -> receive tensors -> expert tensor (implies both) */
+#define FUSCO_DISPATCH_STREAMING 8u /* modifier: write the rows past the memory-side cache (see fusco_dispatch) */
 
 /*
  * Layout descriptor: the two-level descriptor lists of the paper's Communication Planner
@@ -81,6 +82,15 @@ typedef struct fusco_layout {
     int32_t *slot_send_row;  /* [P]    slot -> send row holding its payload                           */
     uint8_t *pair_first;     /* [P]    1 iff the pair is the first appearance of its device in token t */
     int32_t *status;         /* [1]    number of expert ids outside [0, E) seen by the last fusco_plan */
+    /* Transfer order (section 3.2: descriptor lists are dense arrays in transfer order).  The tokens are cut
+     * into tile_count tiles of tile_tokens consecutive tokens (the last one may hold fewer); the entries
+     * [i * tile_tokens * k, (i + 1) * tile_tokens * k) list the slots of tile i's (token, expert) pairs in
+     * ascending order, i.e. expert by expert with ascending tokens inside an expert, followed by -1 up to the
+     * tile's capacity (a ragged last tile, pairs with an invalid expert id).  fusco_dispatch moves the rows
+     * in this order, tile by tile.  tile_tokens and tile_count depend on N and k only and are set by
+     * fusco_layout_bind. */
+    int32_t *tile_slots;     /* [tile_count * tile_tokens * k]                                        */
+    int32_t tile_tokens, tile_count;
 } fusco_layout;
 
 /* Library version (FUSCO_VERSION of the build). */
@@ -141,6 +151,10 @@ int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
  * copy, no intermediate pass): every token row is read once and written to each of its slots,
  *     expert_buf[pair_slot[t*k+j]] = x[t]                          (FUSCO_DISPATCH_EXPERT)
  *     send_buf[pair_send_row[t*k+j]] = x[t] where pair_first       (FUSCO_DISPATCH_WIRE)
+ * For large inputs the expert tensor is written tile by tile in the layout's transfer order (see
+ * fusco_dispatch_in_transfer_order): every XCD of the GPU takes whole tiles of tokens and writes their rows
+ * expert by expert with streaming stores, the tile's source rows being read from HBM once and from the XCD's
+ * L2 afterwards.  Otherwise every token's row is read once and stored to its k rows at once.
  * Rows are opaque bytes.  d_x: [N, row_bytes], row_bytes a positive multiple of 16.  An optional
  * second plane (e.g. per-block scales of an fp8 payload) of aux_row_bytes (multiple of 16, or 0
  * with NULL aux pointers) follows the same descriptors; row_bytes + aux_row_bytes may not exceed
@@ -153,10 +167,25 @@ int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
  *     expert_buf[s] = send_buf[slot_send_row[s]]
  * for every assigned slot.  Both tensors are written and hold the same bytes as in the fused mode;
  * the extra pass costs U + P more row reads.
+ * FUSCO_DISPATCH_STREAMING may be added to the fused modes (not to FUSCO_DISPATCH_TWO_HOP): the same rows are
+ * written with non-temporal stores, which do not stay in the GPU's 256 MB memory-side cache.  Choose it when
+ * other traffic (an expert computation) comes between this call and the first reader of the rows: a plain
+ * dispatch leaves its last ~200 MB of rows dirty in that cache, and whoever streams through memory next pays
+ * for writing them back.  Leave it out when fusco_combine (or any reader) follows at once on these rows: they
+ * are then read from the cache.  Results are identical either way.
  */
 int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
                    void *d_send_aux, uint32_t flags, void *stream);
+
+/*
+ * Host-only: 1 if fusco_dispatch with these row sizes and flags moves the rows tile by tile in the layout's
+ * transfer order (tile_slots), 0 if it walks the tokens, negative on invalid arguments.  The transfer order
+ * is used when only the expert tensor is written, k >= 2, the layout has at least 16 tiles and the source
+ * rows of one tile (tile_tokens * (row_bytes + aux_row_bytes)) fit the 4 MB L2 of an XCD (at most 3840 KiB).
+ * Both ways write the same bytes.
+ */
+int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags);
 
 /*
  * fusco_plan followed by fusco_dispatch (FUSCO_DISPATCH_EXPERT only) in a single launch, for inputs

@@ -52,7 +52,7 @@ def _load():
         for name in ("fusco_oracle_plan", "fusco_oracle_dispatch", "fusco_oracle_dispatch_rows",
                      "fusco_oracle_combine_f64",
                      "fusco_oracle_combine_f32", "fusco_oracle_combine_abs_f64",
-                     "fusco_oracle_combine_two_hop_f32", "fusco_oracle_segments_copy"):
+                     "fusco_oracle_combine_two_hop_f32", "fusco_oracle_segments_copy", "fusco_oracle_tile_order"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -107,6 +107,18 @@ def plan(topk_idx: np.ndarray, E: int, D: int) -> Plan:
     U = int(out["send_off"][D])
     out["send_src"] = out["send_src"][:U]
     return Plan(N=N, k=k, E=E, D=D, pair_first=first, **out)
+
+
+def tile_order(pair_slot: np.ndarray, N: int, k: int, tile_tokens: int) -> np.ndarray:
+    """Transfer order of the expert-tensor rows: per tile of tile_tokens tokens, the slots of its pairs ascending,
+    padded with -1 to tile_tokens * k entries.  int32 [ceil(N / tile_tokens) * tile_tokens * k]."""
+    ps = np.ascontiguousarray(pair_slot, dtype=np.int32)
+    tiles = (N + tile_tokens - 1) // tile_tokens
+    out = np.full(max(tiles * tile_tokens * k, 1), -7, dtype=np.int32)[:tiles * tile_tokens * k]
+    rc = _load().fusco_oracle_tile_order(_p(ps), N, k, tile_tokens, _p(out))
+    if rc != 0:
+        raise ValueError("fusco_oracle_tile_order failed with code %d" % rc)
+    return out
 
 
 def dispatch(pl: Plan, x: np.ndarray, x_aux: Optional[np.ndarray] = None):

@@ -165,6 +165,36 @@ done:
 }
 
 /*
+ * Transfer order of the level-2 descriptors (section 3.2: a descriptor list is a dense array in transfer
+ * order; the paper does not say which order, this is the reading used here).  The tokens are cut into tiles
+ * of tile_tokens consecutive tokens.  The list of a tile holds the rows of the expert-activation tensor that
+ * its (token, expert) pairs own, in ascending row order - so the rows of one expert follow one another, in
+ * ascending token order - and is padded with -1 up to tile_tokens * K entries (a last tile with fewer tokens,
+ * pairs without a row).  tile_slots has ceil(T / tile_tokens) * tile_tokens * K entries.
+ */
+static int cmp_int32(const void *a, const void *b)
+{
+    const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+int fusco_oracle_tile_order(const int32_t *pair_slot, int32_t T, int32_t K, int32_t tile_tokens, int32_t *tile_slots)
+{
+    if (T < 0 || K < 1 || tile_tokens < 1 || (T > 0 && (!pair_slot || !tile_slots))) return ORACLE_ERR_ARG;
+    const int64_t cap = (int64_t)tile_tokens * K;
+    for (int64_t t0 = 0, tile = 0; t0 < T; t0 += tile_tokens, ++tile) {
+        int32_t *list = tile_slots + tile * cap;
+        int64_t n = 0;
+        for (int64_t t = t0; t < t0 + tile_tokens && t < T; ++t)
+            for (int32_t j = 0; j < K; ++j)
+                if (pair_slot[t * K + j] >= 0) list[n++] = pair_slot[t * K + j];
+        qsort(list, (size_t)n, sizeof(int32_t), cmp_int32);
+        for (; n < cap; ++n) list[n] = -1;
+    }
+    return ORACLE_OK;
+}
+
+/*
  * Dispatch, hop by hop as the planner describes it: level 1 moves one row per (token, device)
  * into the device's receive tensor, level 2 moves every (t, e) pair from there to its row of the
  * expert-activation tensor.  Rows are opaque bytes.  send_buf has U = send_off[D] rows,

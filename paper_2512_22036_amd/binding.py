@@ -15,13 +15,13 @@ from typing import Optional
 import torch
 
 BF16, F32 = 0, 1
-DISPATCH_EXPERT, DISPATCH_WIRE, DISPATCH_TWO_HOP = 1, 2, 4
+DISPATCH_EXPERT, DISPATCH_WIRE, DISPATCH_TWO_HOP, DISPATCH_STREAMING = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -39,7 +39,8 @@ class _CLayout(ctypes.Structure):
                 ("pair_slot", ctypes.c_void_p), ("slot_pair", ctypes.c_void_p),
                 ("slot_token", ctypes.c_void_p), ("send_src", ctypes.c_void_p),
                 ("pair_send_row", ctypes.c_void_p), ("slot_send_row", ctypes.c_void_p),
-                ("pair_first", ctypes.c_void_p), ("status", ctypes.c_void_p)]
+                ("pair_first", ctypes.c_void_p), ("status", ctypes.c_void_p),
+                ("tile_slots", ctypes.c_void_p), ("tile_tokens", ctypes.c_int32), ("tile_count", ctypes.c_int32)]
 
 
 _lib = None
@@ -75,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_plan_static.argtypes = [ctypes.POINTER(_CLayout), vp, vp]
     lib.fusco_dispatch.restype = ctypes.c_int
     lib.fusco_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, sz, vp, sz, vp, vp, vp, vp, u32, vp]
+    lib.fusco_dispatch_in_transfer_order.restype = ctypes.c_int
+    lib.fusco_dispatch_in_transfer_order.argtypes = [ctypes.POINTER(_CLayout), sz, sz, u32]
     lib.fusco_plan_dispatch.restype = ctypes.c_int
     lib.fusco_plan_dispatch.argtypes = [ctypes.POINTER(_CLayout), vp, vp, sz, vp, sz, vp, vp, vp]
     lib.fusco_combine.restype = ctypes.c_int
@@ -144,7 +147,7 @@ def fusco_version() -> int:
 
 _I32_FIELDS = {"exp_count": "E", "exp_off": "E+1", "send_count": "D", "send_off": "D+1", "pair_slot": "P",
                "slot_pair": "P", "slot_token": "P", "send_src": "send_cap", "pair_send_row": "P",
-               "slot_send_row": "P", "status": "1"}
+               "slot_send_row": "P", "status": "1", "tile_slots": "tiles"}
 
 
 class Layout:
@@ -163,11 +166,12 @@ class Layout:
                "fusco_layout_bind")
         self.N, self.k, self.E, self.D = N, k, E, D
         self.P, self.send_cap = int(self.c.P), int(self.c.send_cap)
+        self.tile_tokens, self.tile_count = int(self.c.tile_tokens), int(self.c.tile_count)
 
     def array(self, name: str) -> torch.Tensor:
         """Torch view of one descriptor array (int32, or uint8 for pair_first)."""
         sizes = {"E": self.E, "E+1": self.E + 1, "D": self.D, "D+1": self.D + 1, "P": self.P,
-                 "send_cap": self.send_cap, "1": 1}
+                 "send_cap": self.send_cap, "1": 1, "tiles": self.tile_count * self.tile_tokens * self.k}
         off = getattr(self.c, name) - self.mem.data_ptr()
         if name == "pair_first":
             return self.mem[off:off + self.P]
@@ -205,7 +209,7 @@ def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.T
                    flags: int = 0, stream=None) -> None:
     rb = _rows(x, "x", layout.N)
     ab = _rows(x_aux, "x_aux", layout.N) if x_aux is not None else 0
-    eff = flags or DISPATCH_EXPERT
+    eff = (flags & ~DISPATCH_STREAMING) or DISPATCH_EXPERT
     if eff & DISPATCH_TWO_HOP:
         eff |= DISPATCH_EXPERT | DISPATCH_WIRE
     if eff & DISPATCH_EXPERT:
@@ -227,6 +231,13 @@ def fusco_dispatch(layout: Layout, x: torch.Tensor, expert_buf: Optional[torch.T
     _check(load_library().fusco_dispatch(ctypes.byref(layout.c), x.data_ptr(), rb, _ptr(x_aux), ab,
                                          _ptr(expert_buf), _ptr(expert_aux), _ptr(send_buf), _ptr(send_aux),
                                          flags, _stream(stream)), "fusco_dispatch")
+
+
+def fusco_dispatch_in_transfer_order(layout: Layout, row_bytes: int, aux_row_bytes: int = 0, flags: int = 0) -> bool:
+    rc = load_library().fusco_dispatch_in_transfer_order(ctypes.byref(layout.c), row_bytes, aux_row_bytes, flags)
+    if rc < 0:
+        _check(rc, "fusco_dispatch_in_transfer_order")
+    return bool(rc)
 
 
 def fusco_plan_dispatch(layout: Layout, topk_idx: torch.Tensor, x: torch.Tensor, expert_buf: torch.Tensor,

@@ -17,9 +17,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWave = 64;
 constexpr int kPlanThreads = 1024;                      // 16 waves per planner workgroup
 constexpr int kPlanWaves = kPlanThreads / kWave;
-// A planner tile holds R * 1024 (token, expert) pairs, R rounds of 64 pairs per wave.  One round is fastest
-// for the sizes a GPU usually plans at once; two rounds halve the number of tiles of very large inputs and
-// let the single-launch paths take inputs of up to 2048 pairs.  (Four would not fit 64 KiB of LDS.)
+// A planner tile holds R * 1024 (token, expert) pairs, R rounds of 64 pairs per wave: one round for inputs of
+// up to 1024 pairs, two otherwise.  (Four would not fit 64 KiB of LDS.)
 constexpr int kMaxRounds = 2;
 constexpr int kRoundPairs = kPlanThreads;               // pairs of one round of the whole workgroup
 constexpr int kMaxBins = FUSCO_MAX_E;
@@ -59,13 +58,13 @@ inline int single_tile_rounds(int N, int k)
     return 0;
 }
 
-// Rounds per tile of the planner for these sizes: measured on MI355X, one round wins up to a few hundred
-// thousand pairs, two rounds above.
+// Rounds per tile of the planner for these sizes.  A tile is also the unit in which dispatch moves rows
+// (expert by expert inside a tile): two rounds give every expert twice as many neighbouring rows per tile,
+// which is worth more to dispatch (5 us at 8192 tokens x 8) than the 2-3 us the planner loses against one round.
 inline int plan_rounds(int N, int k)
 {
     const int single = single_tile_rounds(N, k);
-    if (single) return single;
-    return (int64_t)N * k <= 393216 ? 1 : 2;
+    return single ? single : kMaxRounds;
 }
 
 // tiles per chunk (a power of two near sqrt(n_tiles)), or 0 when the tiles are few enough to be read one by one

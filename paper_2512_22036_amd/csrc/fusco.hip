@@ -53,12 +53,16 @@ static size_t layout_carve(fusco_layout *L, int32_t N, int32_t k, int32_t E, int
     int32_t *pair_send_row = (int32_t *)take(P * 4);
     int32_t *slot_send_row = (int32_t *)take(P * 4);
     uint8_t *pair_first = (uint8_t *)take(P);
+    const int rounds = plan_rounds(N, k);
+    const int tile_tokens = tokens_per_tile(k, rounds), tile_count = num_tiles(N, k, rounds);
+    int32_t *tile_slots = (int32_t *)take((size_t)tile_count * (size_t)tile_tokens * (size_t)k * 4);
     if (L) {
         L->N = N; L->k = k; L->E = E; L->D = D; L->P = (int32_t)P; L->send_cap = (int32_t)send_cap;
         L->exp_count = exp_count; L->exp_off = exp_off; L->send_count = send_count; L->send_off = send_off;
         L->status = status; L->pair_slot = pair_slot; L->slot_pair = slot_pair; L->slot_token = slot_token;
         L->send_src = send_src; L->pair_send_row = pair_send_row; L->slot_send_row = slot_send_row;
         L->pair_first = pair_first;
+        L->tile_slots = tile_slots; L->tile_tokens = tile_tokens; L->tile_count = tile_count;
     }
     return off;
 }
@@ -90,8 +94,11 @@ static bool layout_ok(const fusco_layout *L)
 {
     if (!L || !sizes_ok(L->N, L->k, L->E, L->D)) return false;
     if ((int64_t)L->P != (int64_t)L->N * L->k) return false;
+    const int rounds = plan_rounds(L->N, L->k);
+    if (L->tile_tokens != tokens_per_tile(L->k, rounds) || L->tile_count != num_tiles(L->N, L->k, rounds)) return false;
     return L->exp_count && L->exp_off && L->send_count && L->send_off && L->pair_slot && L->slot_pair &&
-           L->slot_token && L->send_src && L->pair_send_row && L->slot_send_row && L->pair_first && L->status;
+           L->slot_token && L->send_src && L->pair_send_row && L->slot_send_row && L->pair_first && L->status &&
+           L->tile_slots;
 }
 
 static PlanArgs plan_args(const fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, int rounds)
@@ -111,6 +118,7 @@ static PlanArgs plan_args(const fusco_layout *L, const int32_t *d_topk_idx, void
     a.exp_count = L->exp_count; a.exp_off = L->exp_off; a.send_count = L->send_count; a.send_off = L->send_off;
     a.pair_slot = L->pair_slot; a.slot_pair = L->slot_pair; a.slot_token = L->slot_token; a.send_src = L->send_src;
     a.pair_send_row = L->pair_send_row; a.slot_send_row = L->slot_send_row; a.pair_first = L->pair_first;
+    a.tile_slots = L->tile_slots;
     a.status = L->status;
     return a;
 }
@@ -128,11 +136,10 @@ int fusco_plan(fusco_layout *L, const int32_t *d_topk_idx, void *d_scratch, size
         if (rounds == 1) launch(plan_place_kernel<true, 1>, dim3(1), block, s, a, ev.start, ev.stop);
         else launch(plan_place_kernel<true, 2>, dim3(1), block, s, a, ev.start, ev.stop);
     } else {
-        if (rounds == 1) launch(plan_count_kernel<1>, tiles, block, s, a, ev.start, nullptr);
-        else launch(plan_count_kernel<2>, tiles, block, s, a, ev.start, nullptr);
+        // inputs of several tiles are always planned in tiles of two rounds (plan_rounds)
+        launch(plan_count_kernel<kMaxRounds>, tiles, block, s, a, ev.start, nullptr);
         if (a.n_chunks > 0) launch(plan_chunk_kernel, dim3((unsigned)a.n_chunks), block, s, a);
-        if (rounds == 1) launch(plan_place_kernel<false, 1>, tiles, block, s, a, nullptr, ev.stop);
-        else launch(plan_place_kernel<false, 2>, tiles, block, s, a, nullptr, ev.stop);
+        launch(plan_place_kernel<false, kMaxRounds>, tiles, block, s, a, nullptr, ev.stop);
     }
     return launch_status();
 }
@@ -194,6 +201,7 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
     m.send_buf = nullptr; m.send_aux = nullptr;
     m.pair_slot = L->pair_slot; m.pair_send_row = L->pair_send_row; m.pair_first = L->pair_first;
+    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0; m.n_tiles = 0;
     m.k = L->k;
     m.C = (int32_t)(row_bytes / 16); m.Ca = (int32_t)(aux_row_bytes / 16);
     m.write_expert = 1; m.write_wire = 0;
@@ -210,14 +218,36 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     return launch_status();
 }
 
+// the conditions under which fusco_dispatch moves the rows tile by tile in transfer order
+static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
+                                       bool wire, bool two_hop)
+{
+    const size_t tile_source_bytes = (size_t)L->tile_tokens * (row_bytes + aux_row_bytes);
+    return expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
+           tile_source_bytes <= kTiledMaxTileBytes;
+}
+
+int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags)
+{
+    if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
+    flags &= ~FUSCO_DISPATCH_STREAMING;
+    if (flags == 0) flags = FUSCO_DISPATCH_EXPERT;
+    if (flags & ~(FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE | FUSCO_DISPATCH_TWO_HOP)) return FUSCO_ERR_UNSUPPORTED;
+    return dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, flags & FUSCO_DISPATCH_EXPERT, flags & FUSCO_DISPATCH_WIRE,
+                                      flags & FUSCO_DISPATCH_TWO_HOP) ? 1 : 0;
+}
+
 int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
                    void *d_send_aux, uint32_t flags, void *stream)
 {
     if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
+    const bool streaming = flags & FUSCO_DISPATCH_STREAMING;
+    flags &= ~FUSCO_DISPATCH_STREAMING;
     if (flags == 0) flags = FUSCO_DISPATCH_EXPERT;
     if (flags & ~(FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE | FUSCO_DISPATCH_TWO_HOP)) return FUSCO_ERR_UNSUPPORTED;
     const bool two_hop = flags & FUSCO_DISPATCH_TWO_HOP;
+    if (two_hop && streaming) return FUSCO_ERR_UNSUPPORTED;   // the second hop reads the first hop's rows at once
     if (two_hop) flags |= FUSCO_DISPATCH_EXPERT | FUSCO_DISPATCH_WIRE;   // both tensors are produced
     const bool expert = flags & FUSCO_DISPATCH_EXPERT, wire = flags & FUSCO_DISPATCH_WIRE;
     if (row_bytes == 0 || row_bytes % 16 != 0 || aux_row_bytes % 16 != 0) return FUSCO_ERR_INVALID_ARG;
@@ -236,6 +266,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.expert_buf = (u32x4 *)d_expert_buf; a.expert_aux = (u32x4 *)d_expert_aux;
     a.send_buf = (u32x4 *)d_send_buf; a.send_aux = (u32x4 *)d_send_aux;
     a.pair_slot = L->pair_slot; a.pair_send_row = L->pair_send_row; a.pair_first = L->pair_first;
+    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0; a.n_tiles = 0;
     a.k = L->k;
     a.C = (int32_t)(row_bytes / 16);
     a.Ca = (int32_t)(aux_row_bytes / 16);
@@ -246,14 +277,37 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     int threads = round_up((Ct + cpt - 1) / cpt, kWave);
     if (threads > 256) threads = 256;
     const int segs = (Ct + threads * cpt - 1) / (threads * cpt);
-    const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
     hipStream_t s = (hipStream_t)stream;
     ArmedEvents ev;
     if (two_hop) ev.start = ev.stop = nullptr;   // several kernels: armed events are dropped
-    switch (cpt) {
-    case 1: launch(dispatch_kernel<1>, grid, block, s, a, ev.start, ev.stop); break;
-    case 2: launch(dispatch_kernel<2>, grid, block, s, a, ev.start, ev.stop); break;
-    default: launch(dispatch_kernel<4>, grid, block, s, a, ev.start, ev.stop); break;
+
+    // Expert tensor alone, enough tiles to keep every XCD busy, and a tile's source rows small enough to stay
+    // in one XCD's 4 MB L2: the rows are moved tile by tile in transfer order (dispatch_tiled_kernel).
+    if (dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, expert, wire, two_hop)) {
+        a.slot_token = L->slot_token; a.tile_slots = L->tile_slots;
+        a.tile_cap = L->tile_tokens * L->k; a.n_tiles = L->tile_count;
+        const unsigned rounds_of_tiles = (unsigned)((L->tile_count + kXcds - 1) / kXcds);
+        const dim3 tgrid(rounds_of_tiles * (unsigned)a.tile_cap * kXcds, (unsigned)segs), tblock((unsigned)threads);
+        switch (cpt) {
+        case 1: launch(dispatch_tiled_kernel<1>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+        case 2: launch(dispatch_tiled_kernel<2>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+        default: launch(dispatch_tiled_kernel<4>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+        }
+        return launch_status();
+    }
+    const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
+    if (streaming) {
+        switch (cpt) {
+        case 1: launch(dispatch_kernel<1, true>, grid, block, s, a, ev.start, ev.stop); break;
+        case 2: launch(dispatch_kernel<2, true>, grid, block, s, a, ev.start, ev.stop); break;
+        default: launch(dispatch_kernel<4, true>, grid, block, s, a, ev.start, ev.stop); break;
+        }
+    } else {
+        switch (cpt) {
+        case 1: launch(dispatch_kernel<1>, grid, block, s, a, ev.start, ev.stop); break;
+        case 2: launch(dispatch_kernel<2>, grid, block, s, a, ev.start, ev.stop); break;
+        default: launch(dispatch_kernel<4>, grid, block, s, a, ev.start, ev.stop); break;
+        }
     }
     if (two_hop) {
         // second hop: every row of the expert tensor is pulled from its token's row in the receive

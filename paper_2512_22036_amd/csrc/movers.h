@@ -43,12 +43,28 @@ struct DispatchArgs {
     u32x4 *expert_buf, *expert_aux, *send_buf, *send_aux;
     const int32_t *pair_slot, *pair_send_row;
     const uint8_t *pair_first;
+    const int32_t *slot_token, *tile_slots;   // tiled mode: transfer order of every tile
+    int32_t tile_cap, n_tiles;                // entries per tile in tile_slots, number of tiles
     int32_t k;
     int32_t C, Ca;   // 16-byte chunks per row in the main and in the aux plane
     int32_t write_expert, write_wire;
 };
 
-template <int CPT>
+constexpr int kXcds = 8;                                  // accelerator complexes of an MI355X
+constexpr int kTiledMinTiles = 2 * kXcds;                 // fewer tiles would leave XCDs idle
+constexpr size_t kTiledMaxTileBytes = (size_t)3840 << 10; // source rows of one tile must fit a 4 MB L2
+
+// STREAM: the rows are written with non-temporal stores, which go past the memory-side cache (measured: a
+// read that follows such a write runs at the cold rate, 6.2 TB/s for 256 MB, instead of 4.1 TB/s on rows
+// that sit dirty in that cache).  Right when the rows are not read back soon; slower when they are.
+template <int CPT, bool STREAM>
+__device__ __forceinline__ void put16(u32x4 *p, u32x4 v)
+{
+    if constexpr (STREAM) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+template <int CPT, bool STREAM = false>
 __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 {
     const int t = blockIdx.x;
@@ -69,8 +85,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) a.expert_buf[(size_t)slot * a.C + c] = v[i];
-                else if (c < Ct) a.expert_aux[(size_t)slot * a.Ca + (c - a.C)] = v[i];
+                if (c < a.C) put16<CPT, STREAM>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
+                else if (c < Ct) put16<CPT, STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -83,10 +99,47 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) a.send_buf[(size_t)row * a.C + c] = v[i];
-                else if (c < Ct) a.send_aux[(size_t)row * a.Ca + (c - a.C)] = v[i];
+                if (c < a.C) put16<CPT, STREAM>(a.send_buf + (size_t)row * a.C + c, v[i]);
+                else if (c < Ct) put16<CPT, STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
             }
         }
+    }
+}
+
+// Dispatch in transfer order (the tile_slots list of the planner): one workgroup per destination row.  The
+// hardware hands workgroups to the 8 XCDs in turn, so workgroup b = 8 i + x runs on XCD x; it takes entry
+// i mod cap of tile x + 8 (i / cap).  An XCD therefore works through whole tiles, one after the other, and
+// inside a tile it writes expert by expert: the rows of one expert are neighbours in memory, written by one
+// XCD within a short time, which is what the memory system rewards (measured on MI355X: the same bytes
+// written in runs of 100 KiB and more per XCD reach 6 TB/s and above, isolated 14 KiB rows 5.3 TB/s).  Every
+// source row is needed k times by the tile; it comes from HBM once and from the XCD's L2 afterwards (plain
+// cached loads; a tile's source rows fit the L2), so the fabric still carries every row once.  The rows are
+// written with non-temporal stores: they bypass the L2, which keeps the source rows there, and the
+// memory-side cache, which the next reader of memory would otherwise have to clean first.
+template <int CPT>
+__global__ __launch_bounds__(256) void dispatch_tiled_kernel(DispatchArgs a)
+{
+    const uint32_t b = blockIdx.x, x = b & (kXcds - 1), i = b / kXcds;
+    const uint32_t round = i / (uint32_t)a.tile_cap, r = i - round * (uint32_t)a.tile_cap;
+    const uint32_t tile = x + kXcds * round;
+    if (tile >= (uint32_t)a.n_tiles) return;
+    const int slot = a.tile_slots[(size_t)tile * a.tile_cap + r];
+    if (slot < 0) return;
+    const int t = a.slot_token[slot];
+    const int Ct = a.C + a.Ca;
+    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    u32x4 v[CPT];
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = c0 + q * blockDim.x;
+        if (c < a.C) v[q] = a.x[(size_t)t * a.C + c];
+        else if (c < Ct) v[q] = a.x_aux[(size_t)t * a.Ca + (c - a.C)];
+    }
+#pragma unroll
+    for (int q = 0; q < CPT; ++q) {
+        const int c = c0 + q * blockDim.x;
+        if (c < a.C) __builtin_nontemporal_store(v[q], a.expert_buf + (size_t)slot * a.C + c);
+        else if (c < Ct) __builtin_nontemporal_store(v[q], a.expert_aux + (size_t)slot * a.Ca + (c - a.C));
     }
 }
 

@@ -21,6 +21,7 @@ struct PlanArgs {
     int32_t *chunk_hist;             // [n_chunks][stride]: tile_hist summed over the tiles of a chunk
     int32_t *exp_count, *exp_off, *send_count, *send_off;
     int32_t *pair_slot, *slot_pair, *slot_token, *send_src, *pair_send_row, *slot_send_row;
+    int32_t *tile_slots;   // [n_tiles][tpt * k]: the slots of a tile's pairs in ascending order, then -1
     uint8_t *pair_first;
     int32_t *status;
 };
@@ -172,15 +173,65 @@ struct PlaceLds {
     int invalid;
 };
 
+// Counts of the other tiles, as the placement kernel needs them: thread (part, b) of the workgroup adds up,
+// for key b, the counts of tiles part, part + parts, ... (parts = groups of nb threads that fit the workgroup).
+// The first kCrossE / kCrossD of these loads depend on nothing the workgroup computes; place_tile issues
+// them right after its loads of the routing and uses the values only after the ranking inside the tile, so
+// that one memory latency is paid instead of three in a row (the counts were written by other XCDs in the
+// previous kernel and come from memory).  Not used with a chunk level.
+constexpr int kCrossE = 16, kCrossD = 4;   // 64 tiles of 256 experts / 8 devices are covered without a loop
+
+template <int PF>
+__device__ __forceinline__ void cross_prefetch(const PlanArgs &a, int nb, int hist_off, int (&v)[PF])
+{
+    const int tid = threadIdx.x;
+    const int nb_pad = (nb + kWave - 1) / kWave * kWave;
+    const int parts = kPlanThreads / nb_pad;
+    const int part = tid / nb_pad, b = tid - part * nb_pad;
+    const bool active = a.chunk_tiles == 0 && part < parts && b < nb;
+    const int32_t *h = a.tile_hist + hist_off + b;
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {
+        const int tl = part + i * parts;
+        v[i] = active && tl < a.n_tiles ? h[(int64_t)tl * a.stride] : 0;
+    }
+}
+
+// Exclusive prefix sum of v[0 .. nb) in place, by the calling wave (all 64 lanes): each lane owns a run of
+// consecutive entries; v[nb] receives the total.
+__device__ __forceinline__ void wave_exclusive_scan(int *v, int nb)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int per = (nb + kWave - 1) / kWave;
+    const int lo = min(lane * per, nb), hi = min(lo + per, nb);
+    int sum = 0;
+    for (int b = lo; b < hi; ++b) sum += v[b];
+    int incl = sum;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    int run = incl - sum;
+    for (int b = lo; b < hi; ++b) {
+        const int x = v[b];
+        v[b] = run;
+        run += x;
+    }
+    if (lane == kWave - 1) v[nb] = incl;
+}
+
 // Stable ranking of the tile's participating pairs by key, in pair order, on top of the global
 // order of tiles.  key[r] is the key of pair (wave chunk + r * 64 + lane), or -1 if that pair
 // does not take part.  On return pos[r] is the pair's global position: (global exclusive offset
 // of its key) + (pairs with that key in earlier tiles) + (earlier pairs with that key in this
 // tile).  Block 0 also writes the per-key counts and their exclusive prefix sum.
-template <bool SINGLE, int R>
+// pre_v: the first PF per-tile counts of this thread's key and part (cross_prefetch), all zero otherwise.
+// With TILE_ORDER, tile_pos[r] also receives the pair's position among the tile's own participating pairs in
+// (key, pair) order, and s.total[nb] is left holding their number.
+template <bool SINGLE, int R, int PF, bool TILE_ORDER>
 __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, int tile, bool writer,
-                                            const int (&key)[R], int nb, int hist_off, int32_t *count_out,
-                                            int32_t *off_out, int (&pos)[R])
+                                            const int (&key)[R], int nb, int hist_off, const int (&pre_v)[PF],
+                                            int32_t *count_out, int32_t *off_out, int (&pos)[R], int (&tile_pos)[R])
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int nbits = bits_for(nb);
@@ -225,8 +276,14 @@ __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, i
             const int me = tile;
             int tot = 0, pre = 0;
             if (a.chunk_tiles == 0) {
+                // the first PF tiles of this part were requested at the start of the kernel
+#pragma unroll
+                for (int i = 0; i < PF; ++i) {
+                    tot += pre_v[i];
+                    pre += part + i * parts < me ? pre_v[i] : 0;
+                }
 #pragma unroll 8
-                for (int tl = part; tl < a.n_tiles; tl += parts) {
+                for (int tl = part + PF * parts; tl < a.n_tiles; tl += parts) {
                     const int v = h[(int64_t)tl * a.stride];
                     tot += v;
                     pre += tl < me ? v : 0;
@@ -252,25 +309,8 @@ __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, i
     if (writer && tile == 0)
         for (int b = tid; b < nb; b += kPlanThreads) count_out[b] = s.total[b];
 
-    // exclusive prefix sum over the keys, by wave 0: each lane owns a run of consecutive keys
-    if (wave == 0) {
-        const int per = (nb + kWave - 1) / kWave;
-        const int lo = min(lane * per, nb), hi = min(lo + per, nb);
-        int sum = 0;
-        for (int b = lo; b < hi; ++b) sum += s.total[b];
-        int incl = sum;
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int up = __shfl_up(incl, d, kWave);
-            if (lane >= d) incl += up;
-        }
-        int run = incl - sum;
-        for (int b = lo; b < hi; ++b) {
-            const int v = s.total[b];
-            s.total[b] = run;
-            run += v;
-        }
-        if (lane == kWave - 1) s.total[nb] = incl;
-    }
+    // exclusive prefix sum over the keys, by wave 0
+    if (wave == 0) wave_exclusive_scan(s.total, nb);
     __syncthreads();
     if (writer && tile == 0)
         for (int b = tid; b <= nb; b += kPlanThreads) off_out[b] = s.total[b];
@@ -284,11 +324,20 @@ __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, i
             run += c;
         }
         s.base[b] += s.total[b];
+        if constexpr (TILE_ORDER) s.total[b] = run;   // the global offsets are used up: the tile's own count per key
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < R; ++r)
         pos[r] = key[r] >= 0 ? s.base[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
+    if constexpr (TILE_ORDER) {
+        // the tile's own exclusive prefix over the keys gives the order of its pairs by (key, pair)
+        if (wave == 0) wave_exclusive_scan(s.total, nb);
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            tile_pos[r] = key[r] >= 0 ? s.total[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
+    }
     __syncthreads();
 }
 
@@ -308,12 +357,29 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     if (tid == 0) s.invalid = 0;
     __syncthreads();
     int ekey[R], tl[R];   // expert id and tile-local token of the thread's pairs
+    int eraw[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
+        eraw[r] = p < npairs ? a.A[pair0 + p] : 0;
+    }
+    // counts of the other tiles: requested behind the routing, used after the ranking (see cross_prefetch)
+    int cross_e[kCrossE], cross_d[kCrossD];
+    if constexpr (SINGLE) {
+#pragma unroll
+        for (int i = 0; i < kCrossE; ++i) cross_e[i] = 0;
+#pragma unroll
+        for (int i = 0; i < kCrossD; ++i) cross_d[i] = 0;
+    } else {
+        cross_prefetch<kCrossE>(a, a.E, 0, cross_e);
+        cross_prefetch<kCrossD>(a, a.D, a.E, cross_d);
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
         int key = -1;
         if (p < npairs) {
-            const int e = a.A[pair0 + p];
+            const int e = eraw[r];
             if ((unsigned)e < (unsigned)a.E) key = e;
             else if constexpr (SINGLE) atomicAdd(&s.invalid, 1);
         }
@@ -324,8 +390,9 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     __syncthreads();
 
     // level 2 receive side: expert-major slot of every pair
-    int slot[R];
-    rank_by_key<SINGLE, R>(s, a, tile, writer, ekey, a.E, 0, a.exp_count, a.exp_off, slot);
+    int slot[R], tile_pos[R];
+    rank_by_key<SINGLE, R, kCrossE, true>(s, a, tile, writer, ekey, a.E, 0, cross_e, a.exp_count, a.exp_off, slot, tile_pos);
+    const int tile_pairs = s.total[a.E];          // pairs of this tile with a valid expert id
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
@@ -337,6 +404,16 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
                 a.slot_token[slot[r]] = tok0 + tl[r];
             }
         }
+    }
+    if (writer) {
+        // transfer order of the tile: its slots ascending (expert by expert, tokens ascending), then -1 up to
+        // the tile's capacity
+        const int cap = a.tpt * a.k;
+        int32_t *order = a.tile_slots + (int64_t)tile * cap;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (tile_pos[r] >= 0) order[tile_pos[r]] = slot[r];
+        for (int q = tile_pairs + tid; q < cap; q += kPlanThreads) order[q] = -1;
     }
 
     if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
@@ -353,7 +430,8 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
         dkey[r] = jfirst[r] == p ? d : -1;
     }
     int row[R];
-    rank_by_key<SINGLE, R>(s, a, tile, writer, dkey, a.D, a.E, a.send_count, a.send_off, row);
+    int unused[R];
+    rank_by_key<SINGLE, R, kCrossD, false>(s, a, tile, writer, dkey, a.D, a.E, cross_d, a.send_count, a.send_off, row, unused);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;

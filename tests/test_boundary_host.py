@@ -52,14 +52,14 @@ def test_header_is_plain_c_and_cxx():
 
 
 def test_version_and_status_strings(lib):
-    assert lib.fusco_version() == 100
+    assert lib.fusco_version() == 110
     assert lib.fusco_status_string(0) == b"ok"
     for code in (-1, -2, -3, -4, -99):
         assert len(lib.fusco_status_string(code)) > 0
 
 
 def test_layout_sizes(lib):
-    assert lib.fusco_layout_bytes(8192, 8, 256, 8) >= 4 * (6 * 65536 + 2 * 257 + 2 * 9) + 65536
+    assert lib.fusco_layout_bytes(8192, 8, 256, 8) >= 4 * (7 * 65536 + 2 * 257 + 2 * 9) + 65536
     assert lib.fusco_layout_bytes(0, 8, 256, 8) > 0
     assert lib.fusco_scratch_bytes(8192, 8, 256, 8) >= 32 * (256 + 8 + 1) * 4
     bad = [(-1, 8, 256, 8), (16, 0, 256, 8), (16, 65, 256, 8), (16, 8, 0, 8), (16, 8, 2048, 8),
@@ -79,7 +79,12 @@ def test_layout_bind_carves_disjoint_aligned_arrays(lib):
     assert (L.N, L.k, L.E, L.D, L.P, L.send_cap) == (N, k, E, D, N * k, N * min(k, D))
     sizes = dict(exp_count=4 * E, exp_off=4 * (E + 1), send_count=4 * D, send_off=4 * (D + 1), pair_slot=4 * N * k,
                  slot_pair=4 * N * k, slot_token=4 * N * k, send_src=4 * L.send_cap, pair_send_row=4 * N * k,
-                 slot_send_row=4 * N * k, pair_first=N * k, status=4)
+                 slot_send_row=4 * N * k, pair_first=N * k, status=4,
+                 tile_slots=4 * L.tile_count * L.tile_tokens * k)
+    assert (L.tile_tokens, L.tile_count) == (1024 // k, 1)          # 400 pairs: a single tile of one round
+    L2 = _CLayout()
+    assert lib.fusco_layout_bind(ctypes.byref(L2), 8192, 8, 256, 8, base, lib.fusco_layout_bytes(8192, 8, 256, 8)) == 0
+    assert (L2.tile_tokens, L2.tile_count) == (256, 32)            # tiles of 2048 pairs
     spans = sorted((getattr(L, n), getattr(L, n) + s) for n, s in sizes.items())
     assert spans[0][0] >= base and spans[-1][1] <= base + nbytes
     for (a0, a1), (b0, _) in zip(spans, spans[1:]):
@@ -128,7 +133,9 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert d(buf, 64, None, 0, None, None, None, None, 0, None) == -1            # no expert buffer
     assert d(buf, 64, None, 0, buf, None, None, None, 2, None) == -1             # wire without send buffer
     assert d(buf + 4, 64, None, 0, buf, None, None, None, 0, None) == -1         # misaligned
-    assert d(buf, 64, None, 0, buf, None, None, None, 8, None) == -3             # unknown flag
+    assert d(buf, 64, None, 0, buf, None, None, None, 16, None) == -3            # unknown flag
+    assert d(buf, 64, None, 0, buf, None, buf, None, 4 | 8, None) == -3          # two-hop cannot stream its first hop
+    assert d(buf, 64, None, 0, None, None, None, None, 8, None) == -1            # streaming alone still means the expert tensor
     assert d(buf, 64, None, 0, buf, None, None, None, 4, None) == -1             # two-hop needs the send buffer
     assert d(buf, 16 << 20, None, 0, buf, None, None, None, 0, None) == -1       # row too large
     assert d(buf, (1 << 20) + 16, None, 0, buf, None, None, None, 0, None) == -1 # just above FUSCO_MAX_ROW_BYTES

@@ -51,6 +51,7 @@ def test_full_size_path(fusco, oracle, name, compare_all):
     assert int(got.status[0]) == 0
     for f in PLAN_FIELDS:
         assert np.array_equal(getattr(got, f), getattr(want, f)), f
+    assert np.array_equal(got.tile_slots, oracle.tile_order(want.pair_slot, cfg.N, cfg.k, L.tile_tokens))
 
     # dispatch, expert tensor and wire tensor
     d_e = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")

@@ -53,14 +53,21 @@ def assert_plan_equal(got, want):
         assert np.array_equal(getattr(got, f), getattr(want, f)), f
 
 
+def assert_tile_order(oracle, L, got, want, tag=""):
+    """The transfer order the planner lists for dispatch: per tile of L.tile_tokens tokens, the tile's slots ascending."""
+    ts = oracle.tile_order(want.pair_slot, L.N, L.k, L.tile_tokens)
+    assert L.tile_count == (L.N + L.tile_tokens - 1) // L.tile_tokens or (L.N == 0 and L.tile_count == 1), tag
+    assert np.array_equal(got.tile_slots[:len(ts)], ts), tag
+
+
 PLAN_SHAPES = [
     # N, k, E, D, distinct experts per token
-    # (a planner tile holds 1024 pairs, or 2048 for single-tile inputs and above 393216 pairs)
+    # (a planner tile holds 1024 pairs for inputs of up to 1024 pairs, 2048 pairs otherwise)
     (1, 1, 1, 1, True), (1, 8, 256, 8, True), (5, 2, 4, 2, True), (64, 2, 16, 4, True),
     (128, 8, 256, 8, True),        # exactly one tile of 1024 pairs
     (129, 8, 256, 8, True),        # one tile of 2048 pairs
     (256, 8, 256, 8, True),        # exactly one tile of 2048 pairs
-    (257, 8, 256, 8, True),        # three tiles of 1024 pairs, the last holding one token
+    (257, 8, 256, 8, True),        # two tiles of 2048 pairs, the second holding one token
     (1000, 8, 256, 8, True),       # several tiles, ragged tail
     (4096, 2, 16, 4, True), (3000, 8, 128, 16, True), (777, 6, 96, 12, True),
     (300, 64, 1024, 64, True),     # largest k and E
@@ -68,15 +75,16 @@ PLAN_SHAPES = [
     (900, 4, 64, 1, True),         # single device
     (1300, 5, 10, 5, False),       # repeated experts inside a token
     (2100, 7, 7, 7, False), (129, 33, 66, 2, True),
-    # many tiles: per-tile counts are first summed over chunks of tiles (from 320 tiles of 1024 pairs on)
-    (40832, 8, 256, 8, False),     # 319 tiles: the last size read tile by tile
-    (40833, 8, 256, 8, False),     # 320 tiles, the last one holding one token
-    (30011, 8, 64, 16, True),      # 235 tiles, ragged
-    (5200, 64, 1024, 1024, True),  # 325 tiles, more count columns than threads
-    (49152, 8, 256, 8, False),     # 393216 pairs: the last size planned in tiles of 1024 pairs (384 tiles)
-    (49153, 8, 256, 8, False),     # tiles of 2048 pairs from here on: 193 tiles in chunks of 16
-    (50011, 8, 64, 16, True),      # 196 tiles of 2048 pairs, ragged
-    (600000, 8, 32, 4, False),     # 2344 tiles of 2048 pairs, chunks of 64, last chunk ragged
+    (8192, 8, 256, 8, True),       # 32 tiles: the counts of all other tiles come from the loads issued up front
+    (17000, 8, 256, 8, True),      # 67 tiles: more tiles than those loads cover
+    # many tiles: per-tile counts are first summed over chunks of tiles (from 96 tiles on)
+    (24320, 8, 256, 8, False),     # 95 tiles: the last size read tile by tile
+    (24321, 8, 256, 8, False),     # 96 tiles, the last one holding one token
+    (30011, 8, 64, 16, True),      # 118 tiles, ragged
+    (3300, 64, 1024, 1024, True),  # 104 tiles, more count columns than threads
+    (49153, 8, 256, 8, False),     # 193 tiles in chunks of 16
+    (50011, 8, 64, 16, True),      # 196 tiles, ragged
+    (600000, 8, 32, 4, False),     # 2344 tiles, chunks of 64, last chunk ragged
 ]
 
 
@@ -87,6 +95,7 @@ def test_plan_matches_oracle(fusco, oracle, N, k, E, D, distinct):
     want = oracle.plan(A, E, D)
     assert_plan_equal(got, want)
     assert got.U == want.U
+    assert_tile_order(oracle, L, got, want)
 
 
 def _random_shape(rng):
@@ -123,6 +132,7 @@ def test_random_shapes_whole_path(fusco, oracle):
         tag = "case %d: N=%d k=%d E=%d D=%d distinct=%s C=%d Ca=%d" % (case, N, k, E, D, distinct, C, Ca)
         for f in PLAN_FIELDS:
             assert np.array_equal(getattr(got, f), getattr(want, f)), (tag, f)
+        assert_tile_order(oracle, L, got, want, tag)
         H = C * 8
         xb = W.bf16_bits(rng.standard_normal((N, H)).astype(np.float32))
         eb = torch.zeros((L.P, H), dtype=torch.bfloat16, device="cuda")
@@ -160,6 +170,7 @@ def test_random_shapes_whole_path(fusco, oracle):
             got2 = L2.to_host()
             for f in PLAN_FIELDS:
                 assert np.array_equal(getattr(got2, f), getattr(want, f)), (tag, "fused", f)
+            assert_tile_order(oracle, L2, got2, want, tag)
             assert torch.equal(eb2, eb), tag
             if Ca:
                 assert torch.equal(ea2, ea), tag
@@ -202,6 +213,7 @@ def test_plan_on_full_configs(fusco, oracle, name, n):
     L, got = gpu_plan(fusco, A, cfg.E, cfg.D)
     want = oracle.plan(A, cfg.E, cfg.D)
     assert_plan_equal(got, want)
+    assert_tile_order(oracle, L, got, want)
     check_plan_invariants(got, A)
 
 
@@ -245,7 +257,7 @@ def test_movers_are_deterministic(fusco):
             assert all(torch.equal(a.view(torch.uint8), b.view(torch.uint8)) for a, b in zip(got, ref))
 
 
-@pytest.mark.parametrize("N", [700, 90000, 150000])          # one-level and chunked counts (352 tiles of 1024 pairs)
+@pytest.mark.parametrize("N", [700, 30000, 150000])          # 2 tiles; 59 tiles read one by one; 293 tiles in chunks
 def test_plan_counts_invalid_ids(fusco, oracle, N):
     rng = np.random.default_rng(77)
     k, E, D = 4, 32, 4
@@ -265,6 +277,10 @@ def test_plan_counts_invalid_ids(fusco, oracle, N):
     # valid pairs still form a stable expert-major order among themselves
     order = np.argsort(Ab.reshape(-1)[ok], kind="stable")
     assert np.array_equal(got.slot_pair[:N * k - 9], np.flatnonzero(ok)[order])
+    # the transfer order lists the valid pairs' rows only (expected slots built here from the stable order above)
+    slot_of = np.full(N * k, -1, dtype=np.int32)
+    slot_of[np.flatnonzero(ok)[order]] = np.arange(N * k - 9, dtype=np.int32)
+    assert np.array_equal(got.tile_slots, oracle.tile_order(slot_of, N, k, L.tile_tokens))
     # the movers skip invalid pairs instead of faulting
     x = bf16_dev(W.bf16_bits(rng.standard_normal((N, 64)).astype(np.float32)))
     eb = torch.zeros((N * k, 64), dtype=torch.bfloat16, device="cuda")
@@ -288,8 +304,9 @@ DISPATCH_SHAPES = [
 
 
 @pytest.mark.parametrize("N,k,E,D,row_bytes", DISPATCH_SHAPES)
-@pytest.mark.parametrize("flags", [0, 2, 3])
+@pytest.mark.parametrize("flags", [0, 2, 3, 8, 8 + 2, 8 + 3])      # 8: the same rows written with streaming stores
 def test_dispatch_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, flags):
+    streaming, flags = flags & 8, flags & 7
     rng = np.random.default_rng(N + row_bytes)
     A = random_topk(rng, N, k, E)
     x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
@@ -298,7 +315,8 @@ def test_dispatch_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, flags):
     L, got = gpu_plan(fusco, A, E, D)
     eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
     sb = torch.full((L.send_cap, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
-    fusco.fusco_dispatch(L, dev(x), eb if flags != 2 else None, send_buf=sb if flags & 2 else None, flags=flags)
+    fusco.fusco_dispatch(L, dev(x), eb if flags != 2 else None, send_buf=sb if flags & 2 else None,
+                         flags=flags | streaming)
     torch.cuda.synchronize()
     if flags != 2:
         assert np.array_equal(eb.cpu().numpy(), expert_want)
@@ -565,3 +583,85 @@ def test_binding_rejects_wrong_shapes(fusco):
                             torch.zeros((16, 2), device="cuda"), torch.zeros((16, 32), dtype=torch.bfloat16, device="cuda"))
     with pytest.raises(fusco.FuscoError):
         fusco.Layout(16, 2, 4, 3)
+
+
+TILED_SHAPES = [
+    # N, k, E, D, row_bytes, aux_row_bytes, distinct: inputs of at least 16 tiles of 2048 pairs whose tile of source
+    # rows fits an XCD's L2, so that dispatch moves the rows in transfer order
+    (4100, 8, 64, 8, 2048, 0, True),          # 17 tiles, the last one ragged; one XCD gets three tiles, the others two
+    (3000, 16, 128, 16, 20480, 0, True),      # rows longer than one workgroup column (1280 chunks): two columns
+    (20000, 2, 16, 4, 48, 16, True),          # tiny rows and a second plane, 1024 tokens per tile
+    (1100, 64, 1024, 64, 512, 0, True),       # 35 tiles of 32 tokens, largest k
+    (5000, 8, 256, 8, 14336, 224, True),      # the benchmark's rows plus a plane of scales: 3.7 MB of source per tile
+    (6000, 6, 10, 5, 256, 0, False),          # repeated experts inside a token
+    (8192, 8, 256, 8, 4096, 0, True),         # exactly 32 full tiles
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", TILED_SHAPES)
+def test_dispatch_in_transfer_order_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, aux_bytes, distinct):
+    rng = np.random.default_rng(N + row_bytes)
+    A = random_topk(rng, N, k, E, distinct)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    xa = rng.integers(0, 256, size=(N, aux_bytes), dtype=np.uint8) if aux_bytes else None
+    want = oracle.plan(A, E, D)
+    L, got = gpu_plan(fusco, A, E, D)
+    assert_plan_equal(got, want)
+    assert_tile_order(oracle, L, got, want)
+    assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes, aux_bytes)           # the path under test
+    assert not fusco.fusco_dispatch_in_transfer_order(L, row_bytes, aux_bytes, 3)    # with the wire tensor: token walk
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    ea = torch.full((L.P, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda") if aux_bytes else None
+    fusco.fusco_dispatch(L, dev(x), eb, x_aux=dev(xa) if aux_bytes else None, expert_aux=ea)
+    torch.cuda.synchronize()
+    if aux_bytes:
+        _, expert_want, _, eaux_want = oracle.dispatch(want, x, xa)
+        assert np.array_equal(ea.cpu().numpy(), eaux_want)
+    else:
+        _, expert_want = oracle.dispatch(want, x)
+    assert np.array_equal(eb.cpu().numpy(), expert_want)
+    # the token walk (chosen here by asking for the wire tensor as well) writes the same expert tensor
+    eb2 = torch.full_like(eb, 0x11)
+    sb = torch.empty((L.send_cap, row_bytes), dtype=torch.uint8, device="cuda")
+    sa = torch.empty((L.send_cap, aux_bytes), dtype=torch.uint8, device="cuda") if aux_bytes else None
+    ea2 = torch.full_like(ea, 0x11) if aux_bytes else None
+    fusco.fusco_dispatch(L, dev(x), eb2, x_aux=dev(xa) if aux_bytes else None, expert_aux=ea2, send_buf=sb, send_aux=sa,
+                         flags=3)
+    torch.cuda.synchronize()
+    assert torch.equal(eb2, eb) and (not aux_bytes or torch.equal(ea2, ea))
+
+
+def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle):
+    rng = np.random.default_rng(5)
+    N, k, E, D, row_bytes = 5000, 8, 64, 8, 1024
+    A = random_topk(rng, N, k, E).reshape(-1)
+    bad = rng.choice(N * k, size=40, replace=False)
+    A[bad[:20]] = E
+    A[bad[20:]] = -5
+    A = A.reshape(N, k)
+    L, got = gpu_plan(fusco, A, E, D)
+    assert int(got.status[0]) == 40 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    fusco.fusco_dispatch(L, dev(x), eb)
+    torch.cuda.synchronize()
+    ebh = eb.cpu().numpy()
+    ok = np.ones(N * k, dtype=bool)
+    ok[bad] = False
+    order = np.flatnonzero(ok)[np.argsort(A.reshape(-1)[ok], kind="stable")]      # pairs in expert-major order
+    assert np.array_equal(ebh[:len(order)], x[order // k])
+    assert np.all(ebh[len(order):] == 0xEE)                                      # rows nobody owns stay untouched
+
+
+def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(fusco):
+    small = fusco.Layout(1000, 8, 64, 8)             # 4 tiles: too few for the eight XCDs
+    many = fusco.Layout(8192, 8, 256, 8)             # 32 tiles of 256 tokens
+    top1 = fusco.Layout(65536, 1, 64, 8)             # k = 1: a row is used once, nothing to keep in the L2
+    assert not fusco.fusco_dispatch_in_transfer_order(small, 2048)
+    assert fusco.fusco_dispatch_in_transfer_order(many, 14336)
+    assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 224)
+    assert fusco.fusco_dispatch_in_transfer_order(many, 15360) and not fusco.fusco_dispatch_in_transfer_order(many, 15376)
+    assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_WIRE)
+    assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
+    assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_STREAMING)
+    assert not fusco.fusco_dispatch_in_transfer_order(top1, 2048)

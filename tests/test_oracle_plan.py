@@ -143,3 +143,42 @@ def test_rejects_bad_arguments(oracle):
         oracle.plan(np.array([[0, -1]], dtype=np.int32), 8, 2)
     with pytest.raises(ValueError):
         oracle.plan(np.array([[0, 1]], dtype=np.int32), 8, 3)      # E % D != 0
+
+
+# ---- transfer order of the expert-tensor rows (tiles of tokens, rows ascending inside a tile) ----
+
+def _tile_order_by_definition(pair_slot, N, k, tile_tokens):
+    out = []
+    for t0 in range(0, N, tile_tokens):
+        mine = sorted(int(s) for s in pair_slot[t0 * k:min(t0 + tile_tokens, N) * k] if s >= 0)
+        out += mine + [-1] * (tile_tokens * k - len(mine))
+    return np.array(out, dtype=np.int32)
+
+
+@pytest.mark.parametrize("N,k,E,D,tile_tokens", [(1, 1, 1, 1, 1), (10, 2, 4, 2, 4), (37, 3, 9, 3, 8), (64, 8, 32, 4, 16),
+                                                 (100, 4, 16, 4, 100), (100, 4, 16, 4, 1000), (33, 5, 5, 5, 7)])
+def test_tile_order_matches_its_definition(oracle, N, k, E, D, tile_tokens):
+    rng = np.random.default_rng(N * 7 + tile_tokens)
+    A = random_topk(rng, N, k, E, distinct=k <= E)
+    pl = oracle.plan(A, E, D)
+    got = oracle.tile_order(pl.pair_slot, N, k, tile_tokens)
+    assert np.array_equal(got, _tile_order_by_definition(pl.pair_slot, N, k, tile_tokens))
+    # every row of the expert tensor is listed exactly once, by the tile of its token, experts ascending inside a tile
+    listed = got[got >= 0]
+    assert np.array_equal(np.sort(listed), np.arange(pl.P))
+    cap = tile_tokens * k
+    for i in range(len(got) // cap):
+        rows = got[i * cap:(i + 1) * cap]
+        rows = rows[rows >= 0]
+        assert np.all(np.diff(rows) > 0)
+        assert np.all(pl.slot_token[rows] // tile_tokens == i)
+        experts = A.reshape(-1)[pl.slot_pair[rows]]
+        assert np.all(np.diff(experts) >= 0)
+
+
+def test_tile_order_skips_pairs_without_a_row_and_handles_one_tile(oracle):
+    ps = np.array([5, -1, 0, 3, -1, -1, 2, 1], dtype=np.int32)             # 4 tokens x 2, three pairs without a row
+    assert oracle.tile_order(ps, 4, 2, 2).tolist() == [0, 3, 5, -1, 1, 2, -1, -1]
+    assert oracle.tile_order(ps, 4, 2, 4).tolist() == [0, 1, 2, 3, 5, -1, -1, -1]
+    assert oracle.tile_order(ps, 4, 2, 3).tolist() == [0, 3, 5, -1, -1, -1, 1, 2, -1, -1, -1, -1]
+    assert oracle.tile_order(np.zeros(0, dtype=np.int32), 0, 2, 4).tolist() == []

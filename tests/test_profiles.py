@@ -1,0 +1,32 @@
+"""The tracked profiler summaries that bench.py and the design notes quote must belong to the kernels in the tree:
+the HBM-traffic summary names the mover source it was taken with, and bench.py reads its figures from it."""
+import hashlib
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+TRAFFIC = os.path.join(ROOT, "profiles", "bench_dsv3_hbm_traffic_pmc.txt")
+MOVERS = os.path.join(ROOT, "paper_2512_22036_amd", "csrc", "movers.h")
+
+
+def test_traffic_summary_was_taken_with_the_movers_in_the_tree():
+    text = open(TRAFFIC).read()
+    m = re.search(r"^movers\.h sha256: ([0-9a-f]{64})$", text, flags=re.M)
+    assert m, "the summary must name the mover source it was measured with"
+    assert m.group(1) == hashlib.sha256(open(MOVERS, "rb").read()).hexdigest(), \
+        "csrc/movers.h changed since profiles/bench_dsv3_hbm_traffic_pmc.txt was taken: profile again"
+
+
+def test_bench_reads_its_traffic_figures_from_the_summary():
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    got = bench.measured_traffic("dsv3")
+    algorithmic = (8192 + 65536) * 14336
+    assert set(got) == {"dispatch", "combine"}
+    for kernel, nbytes in got.items():
+        # every row once: no wasted re-reads, and nothing the counters could have missed
+        assert algorithmic <= nbytes <= 1.01 * algorithmic, (kernel, nbytes)
+    assert bench.measured_traffic("qwen3") == {}          # no summary for other workloads: reported as null
+    assert "MEASURED_TRAFFIC_BYTES" not in open(os.path.join(ROOT, "bench.py")).read()
