@@ -397,23 +397,7 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
         s.tile_slot[p] = slot[r];
-        if (writer && p < npairs) {
-            a.pair_slot[pair0 + p] = slot[r];
-            if (slot[r] >= 0) {
-                a.slot_pair[slot[r]] = (int32_t)(pair0 + p);
-                a.slot_token[slot[r]] = tok0 + tl[r];
-            }
-        }
-    }
-    if (writer) {
-        // transfer order of the tile: its slots ascending (expert by expert, tokens ascending), then -1 up to
-        // the tile's capacity
-        const int cap = a.tpt * a.k;
-        int32_t *order = a.tile_slots + (int64_t)tile * cap;
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (tile_pos[r] >= 0) order[tile_pos[r]] = slot[r];
-        for (int q = tile_pairs + tid; q < cap; q += kPlanThreads) order[q] = -1;
+        if (writer && p < npairs) a.pair_slot[pair0 + p] = slot[r];
     }
 
     if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
@@ -444,16 +428,42 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     __syncthreads();
 
     // level 2 send side: every pair points at the send row of its token on its device
+    int srow[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
-        if (!writer || p >= npairs) continue;
-        int srow = -1;
-        if (ekey[r] >= 0) {
-            srow = s.tile_row[jfirst[r]];
-            a.slot_send_row[slot[r]] = srow;
+        srow[r] = ekey[r] >= 0 ? s.tile_row[jfirst[r]] : -1;
+        if (p < npairs) a.pair_send_row[pair0 + p] = srow[r];
+    }
+    // The arrays indexed by slot are written in the tile's transfer order (its slots ascending: expert by expert,
+    // tokens ascending), which is also the order that is listed for dispatch: neighbouring threads then write
+    // neighbouring slots of one expert, a few cache lines per wave instead of 64.  The pairs meet their place in
+    // that order through LDS; sorted_pair reuses the per-wave counters, which the ranking no longer needs.
+    uint16_t *sorted_pair = &s.wave_cnt[0][0];
+    static_assert(sizeof(s.wave_cnt) >= R * kRoundPairs * sizeof(uint16_t), "sorted_pair fits the per-wave counters");
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
+        if (tile_pos[r] >= 0) {
+            sorted_pair[tile_pos[r]] = (uint16_t)p;
+            // only pairs that are not a first appearance write here, and nobody reads their entry above
+            if (jfirst[r] != p) s.tile_row[p] = srow[r];
         }
-        a.pair_send_row[pair0 + p] = srow;
+    }
+    __syncthreads();
+    const int cap = a.tpt * a.k;
+    int32_t *order = a.tile_slots + (int64_t)tile * cap;
+    for (int q = tid; q < cap; q += kPlanThreads) {
+        if (q < tile_pairs) {
+            const int p = sorted_pair[q];
+            const int sl = s.tile_slot[p];
+            order[q] = sl;
+            a.slot_pair[sl] = (int32_t)(pair0 + p);
+            a.slot_token[sl] = tok0 + div20(p, a.k_magic);
+            a.slot_send_row[sl] = s.tile_row[p];
+        } else {
+            order[q] = -1;
+        }
     }
 
     if (writer && tile == 0 && wave == 0) {
