@@ -171,15 +171,16 @@ struct PlaceLds {
     int base[kMaxBins];                        // per key: pairs in earlier tiles, then the tile's global start
     int total[kMaxBins + 1];
     int invalid;
+    int tile_pairs;                            // pairs of the tile with a valid expert id
 };
 
 // Counts of the other tiles, as the placement kernel needs them: thread (part, b) of the workgroup adds up,
 // for key b, the counts of tiles part, part + parts, ... (parts = groups of nb threads that fit the workgroup).
-// The first kCrossE / kCrossD of these loads depend on nothing the workgroup computes; place_tile issues
+// The first kCross of these loads depend on nothing the workgroup computes; place_tile issues
 // them right after its loads of the routing and uses the values only after the ranking inside the tile, so
 // that one memory latency is paid instead of three in a row (the counts were written by other XCDs in the
 // previous kernel and come from memory).  Not used with a chunk level.
-constexpr int kCrossE = 16, kCrossD = 4;   // 64 tiles of 256 experts / 8 devices are covered without a loop
+constexpr int kCross = 16;   // 48 tiles of 256 experts + 8 devices are covered without a loop
 
 template <int PF>
 __device__ __forceinline__ void cross_prefetch(const PlanArgs &a, int nb, int hist_off, int (&v)[PF])
@@ -198,8 +199,8 @@ __device__ __forceinline__ void cross_prefetch(const PlanArgs &a, int nb, int hi
 }
 
 // Exclusive prefix sum of v[0 .. nb) in place, by the calling wave (all 64 lanes): each lane owns a run of
-// consecutive entries; v[nb] receives the total.
-__device__ __forceinline__ void wave_exclusive_scan(int *v, int nb)
+// consecutive entries; *total receives the sum.
+__device__ __forceinline__ void wave_exclusive_scan(int *v, int nb, int *total)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int per = (nb + kWave - 1) / kWave;
@@ -217,43 +218,57 @@ __device__ __forceinline__ void wave_exclusive_scan(int *v, int nb)
         v[b] = run;
         run += x;
     }
-    if (lane == kWave - 1) v[nb] = incl;
+    if (lane == kWave - 1) *total = incl;
 }
 
-// Stable ranking of the tile's participating pairs by key, in pair order, on top of the global
-// order of tiles.  key[r] is the key of pair (wave chunk + r * 64 + lane), or -1 if that pair
-// does not take part.  On return pos[r] is the pair's global position: (global exclusive offset
-// of its key) + (pairs with that key in earlier tiles) + (earlier pairs with that key in this
-// tile).  Block 0 also writes the per-key counts and their exclusive prefix sum.
-// pre_v: the first PF per-tile counts of this thread's key and part (cross_prefetch), all zero otherwise.
-// With TILE_ORDER, tile_pos[r] also receives the pair's position among the tile's own participating pairs in
-// (key, pair) order, and s.total[nb] is left holding their number.
-template <bool SINGLE, int R, int PF, bool TILE_ORDER>
-__device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, int tile, bool writer,
-                                            const int (&key)[R], int nb, int hist_off, const int (&pre_v)[PF],
-                                            int32_t *count_out, int32_t *off_out, int (&pos)[R], int (&tile_pos)[R])
+// Clears the counters of rank_bins for nb bins.  The caller puts a barrier between this and rank_bins.
+template <int R>
+__device__ __forceinline__ void rank_clear(PlaceLds<R> &s, int nb)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int nbits = bits_for(nb);
-    const uint64_t lt = ((uint64_t)1 << lane) - 1;
-
     for (int b = lane; b < nb; b += kWave) s.wave_cnt[wave][b] = 0;
     for (int b = tid; b < nb; b += kPlanThreads) {
         s.total[b] = 0;
         s.base[b] = 0;
     }
-    __syncthreads();
+}
 
-    // rank inside the wave's chunk; wave_cnt[wave][key] is the running count of the key
-    int rank[R];
+// Stable ranking of the tile's pairs by key, in pair order, on top of the global order of tiles.
+// The bins are nE expert bins followed by nD device bins (either may be 0): expert keys are ranked into
+// slots of the expert-activation tensor, device keys (first appearances only) into send rows, in one
+// pass over a common set of counters.  key[i] is a bin, or -1 for an entry that does not take part; the
+// thread's NK entries are ranked in the order i = 0 .. NK-1, each index being one round of 64 consecutive
+// pairs of the wave.  On return pos[i] is the entry's global position inside its own family: (exclusive
+// offset of the key among the experts, or among the devices) + (entries with that key in earlier tiles) +
+// (earlier entries with that key in this tile).  tile_pos[i] is, for expert keys, the position among the
+// tile's own pairs in (expert, pair) order; s.tile_pairs receives their number.  Block 0 also writes the
+// per-key counts and their exclusive prefix sums.  hist_off: column of bin 0 in the per-tile counts.
+// pre_v: the first PF per-tile counts of this thread's key and part (cross_prefetch).
+template <bool SINGLE, int R, int NK, int PF>
+__device__ __forceinline__ void rank_bins(PlaceLds<R> &s, const PlanArgs &a, int tile, bool writer, const int (&key)[NK],
+                                          int nE, int nD, int hist_off, const int (&pre_v)[PF], int (&pos)[NK],
+                                          int (&tile_pos)[NK])
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int nb = nE + nD;
+    // entries of one index i are all expert keys (i < expert_rounds) or all device keys, so lanes with the
+    // same key are found by comparing only as many bits as that family has
+    const int expert_rounds = nE == 0 ? 0 : (nD == 0 ? NK : NK / 2);
+    const int ebits = bits_for(nE), dbits = bits_for(nD);
+    const uint64_t lt = ((uint64_t)1 << lane) - 1;
+    int *tile_cnt = s.tile_row;   // the tile's own count per expert, then their prefix: tile_row is written later
+
+    // rank inside the wave's chunk; wave_cnt[wave][key] is the running count of the key (zero on entry:
+    // rank_clear, and a barrier, come before this call)
+    int rank[NK];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const bool part = key[r] >= 0;
-        const uint64_t m = same_key_lanes(key[r], part, nbits);
-        const int before = part ? s.wave_cnt[wave][key[r]] : 0;
-        rank[r] = before + __builtin_popcountll(m & lt);
+    for (int i = 0; i < NK; ++i) {
+        const bool part = key[i] >= 0;
+        const uint64_t m = i < expert_rounds ? same_key_lanes(key[i], part, ebits) : same_key_lanes(key[i] - nE, part, dbits);
+        const int before = part ? s.wave_cnt[wave][key[i]] : 0;
+        rank[i] = before + __builtin_popcountll(m & lt);
         wave_lds_order();
-        if (part && (m & lt) == 0) s.wave_cnt[wave][key[r]] = (uint16_t)(before + __builtin_popcountll(m));
+        if (part && (m & lt) == 0) s.wave_cnt[wave][key[i]] = (uint16_t)(before + __builtin_popcountll(m));
         wave_lds_order();
     }
     __syncthreads();
@@ -307,15 +322,23 @@ __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, i
     }
     __syncthreads();
     if (writer && tile == 0)
-        for (int b = tid; b < nb; b += kPlanThreads) count_out[b] = s.total[b];
+        for (int b = tid; b < nb; b += kPlanThreads) {
+            if (b < nE) a.exp_count[b] = s.total[b];
+            else a.send_count[b - nE] = s.total[b];
+        }
 
-    // exclusive prefix sum over the keys, by wave 0
-    if (wave == 0) wave_exclusive_scan(s.total, nb);
+    // exclusive prefix sum over all bins, by wave 0; the devices' offsets start after the experts' total
+    if (wave == 0) wave_exclusive_scan(s.total, nb, &s.total[nb]);
     __syncthreads();
+    const int experts_total = s.total[nE];   // 0 when there are no expert bins
     if (writer && tile == 0)
-        for (int b = tid; b <= nb; b += kPlanThreads) off_out[b] = s.total[b];
+        for (int b = tid; b <= nb; b += kPlanThreads) {
+            if (nE > 0 && b <= nE) a.exp_off[b] = s.total[b];
+            if (nD > 0 && b >= nE) a.send_off[b - nE] = s.total[b] - experts_total;
+        }
 
-    // per key: prefix of the per-wave counts, and the global position where the tile's run starts
+    // per key: prefix of the per-wave counts, the global position where the tile's run starts, and the
+    // tile's own count per expert
     for (int b = tid; b < nb; b += kPlanThreads) {
         int run = 0;
         for (int w = 0; w < kPlanWaves; ++w) {
@@ -323,21 +346,19 @@ __device__ __forceinline__ void rank_by_key(PlaceLds<R> &s, const PlanArgs &a, i
             s.wave_cnt[w][b] = (uint16_t)run;
             run += c;
         }
-        s.base[b] += s.total[b];
-        if constexpr (TILE_ORDER) s.total[b] = run;   // the global offsets are used up: the tile's own count per key
+        s.base[b] += s.total[b] - (b >= nE ? experts_total : 0);
+        if (b < nE) tile_cnt[b] = run;
     }
     __syncthreads();
+    // the tile's own exclusive prefix over the experts gives the order of its pairs by (expert, pair)
+    if (wave == 0 && nE > 0) wave_exclusive_scan(tile_cnt, nE, &s.tile_pairs);
 #pragma unroll
-    for (int r = 0; r < R; ++r)
-        pos[r] = key[r] >= 0 ? s.base[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
-    if constexpr (TILE_ORDER) {
-        // the tile's own exclusive prefix over the keys gives the order of its pairs by (key, pair)
-        if (wave == 0) wave_exclusive_scan(s.total, nb);
-        __syncthreads();
+    for (int i = 0; i < NK; ++i)
+        pos[i] = key[i] >= 0 ? s.base[key[i]] + s.wave_cnt[wave][key[i]] + rank[i] : -1;
+    __syncthreads();
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            tile_pos[r] = key[r] >= 0 ? s.total[key[r]] + s.wave_cnt[wave][key[r]] + rank[r] : -1;
-    }
+    for (int i = 0; i < NK; ++i)
+        tile_pos[i] = key[i] >= 0 && key[i] < nE ? tile_cnt[key[i]] + s.wave_cnt[wave][key[i]] + rank[i] : -1;
     __syncthreads();
 }
 
@@ -353,6 +374,8 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     const int ntok = min(a.tpt, a.N - tok0);
     const int npairs = ntok > 0 ? ntok * a.k : 0;
     const int64_t pair0 = (int64_t)tok0 * a.k;
+    // experts and devices share one ranking pass when their bins fit the counters together
+    const bool together = a.E + a.D <= kMaxBins;
 
     if (tid == 0) s.invalid = 0;
     __syncthreads();
@@ -364,16 +387,14 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
         eraw[r] = p < npairs ? a.A[pair0 + p] : 0;
     }
     // counts of the other tiles: requested behind the routing, used after the ranking (see cross_prefetch)
-    int cross_e[kCrossE], cross_d[kCrossD];
+    int cross[kCross];
     if constexpr (SINGLE) {
 #pragma unroll
-        for (int i = 0; i < kCrossE; ++i) cross_e[i] = 0;
-#pragma unroll
-        for (int i = 0; i < kCrossD; ++i) cross_d[i] = 0;
+        for (int i = 0; i < kCross; ++i) cross[i] = 0;
     } else {
-        cross_prefetch<kCrossE>(a, a.E, 0, cross_e);
-        cross_prefetch<kCrossD>(a, a.D, a.E, cross_d);
+        cross_prefetch<kCross>(a, together ? a.E + a.D : a.E, 0, cross);
     }
+    rank_clear(s, together ? a.E + a.D : a.E);   // while the loads are on their way
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
@@ -389,20 +410,7 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
     }
     __syncthreads();
 
-    // level 2 receive side: expert-major slot of every pair
-    int slot[R], tile_pos[R];
-    rank_by_key<SINGLE, R, kCrossE, true>(s, a, tile, writer, ekey, a.E, 0, cross_e, a.exp_count, a.exp_off, slot, tile_pos);
-    const int tile_pairs = s.total[a.E];          // pairs of this tile with a valid expert id
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int p = wave * (R * kWave) + r * kWave + lane;
-        s.tile_slot[p] = slot[r];
-        if (writer && p < npairs) a.pair_slot[pair0 + p] = slot[r];
-    }
-
-    if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
-
-    // level 1: one send row per (token, device), taken at the device's first appearance
+    // level 1: a token has one send row per device, taken at the device's first appearance among its entries
     const int dbits = bits_for(a.D);
     int dkey[R], jfirst[R];   // jfirst: the token's first pair on the same device
 #pragma unroll
@@ -413,14 +421,52 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
         jfirst[r] = first_pair_on_device(s.tile_dev, p, lane, tl[r] * a.k, d, dbits, same);
         dkey[r] = jfirst[r] == p ? d : -1;
     }
-    int row[R];
-    int unused[R];
-    rank_by_key<SINGLE, R, kCrossD, false>(s, a, tile, writer, dkey, a.D, a.E, cross_d, a.send_count, a.send_off, row, unused);
+
+    // level 2 receive side (expert-major slot of every pair) and level 1 (send row of every first appearance)
+    int slot[R], tile_pos[R], row[R];
+    if (together) {
+        int key2[2 * R], pos2[2 * R], tp2[2 * R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            key2[r] = ekey[r];
+            key2[R + r] = dkey[r] >= 0 ? a.E + dkey[r] : -1;
+        }
+        rank_bins<SINGLE, R, 2 * R, kCross>(s, a, tile, writer, key2, a.E, a.D, 0, cross, pos2, tp2);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            slot[r] = pos2[r];
+            tile_pos[r] = tp2[r];
+            row[r] = pos2[R + r];
+        }
+    } else {
+        int unused[R];
+        rank_bins<SINGLE, R, R, kCross>(s, a, tile, writer, ekey, a.E, 0, 0, cross, slot, tile_pos);
+        int cross_d[kCross];   // (the second pass has no expert bins and leaves s.tile_pairs alone)
+        if constexpr (SINGLE) {
+#pragma unroll
+            for (int i = 0; i < kCross; ++i) cross_d[i] = 0;
+        } else {
+            cross_prefetch<kCross>(a, a.D, a.E, cross_d);
+        }
+        rank_clear(s, a.D);
+        __syncthreads();
+        rank_bins<SINGLE, R, R, kCross>(s, a, tile, writer, dkey, 0, a.D, a.E, cross_d, row, unused);
+    }
+    const int tile_pairs = s.tile_pairs;          // pairs of this tile with a valid expert id
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int p = wave * (R * kWave) + r * kWave + lane;
+        s.tile_slot[p] = slot[r];
+        if (writer && p < npairs) a.pair_slot[pair0 + p] = slot[r];
+    }
+
+    if (!writer) return;   // only the slots are wanted (uniform over the workgroup)
+
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = wave * (R * kWave) + r * kWave + lane;
         s.tile_row[p] = row[r];
-        if (writer && p < npairs) {
+        if (p < npairs) {
             a.pair_first[pair0 + p] = row[r] >= 0 ? 1 : 0;
             if (row[r] >= 0) a.send_src[row[r]] = tok0 + tl[r];
         }
@@ -466,7 +512,7 @@ __device__ __forceinline__ void place_tile(PlaceLds<R> &s, const PlanArgs &a, in
         }
     }
 
-    if (writer && tile == 0 && wave == 0) {
+    if (tile == 0 && wave == 0) {
         int bad = 0;
         if constexpr (SINGLE) {
             bad = s.invalid;
