@@ -288,10 +288,18 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
         a.tile_cap = L->tile_tokens * L->k; a.n_tiles = L->tile_count;
         const unsigned rounds_of_tiles = (unsigned)((L->tile_count + kXcds - 1) / kXcds);
         const dim3 tgrid(rounds_of_tiles * (unsigned)a.tile_cap * kXcds, (unsigned)segs), tblock((unsigned)threads);
-        switch (cpt) {
-        case 1: launch(dispatch_tiled_kernel<1>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-        case 2: launch(dispatch_tiled_kernel<2>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-        default: launch(dispatch_tiled_kernel<4>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+        if (a.Ca) {
+            switch (cpt) {
+            case 1: launch(dispatch_tiled_kernel<1, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            case 2: launch(dispatch_tiled_kernel<2, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            default: launch(dispatch_tiled_kernel<4, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            }
+        } else {
+            switch (cpt) {
+            case 1: launch(dispatch_tiled_kernel<1, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            case 2: launch(dispatch_tiled_kernel<2, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            default: launch(dispatch_tiled_kernel<4, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            }
         }
         return launch_status();
     }
