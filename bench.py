@@ -41,7 +41,7 @@ def measured_traffic(workload: str):
         return out
     for l in lines:
         f = l.split()
-        if len(f) >= 5 and f[0] in ("dispatch_kernel", "combine_kernel"):
+        if len(f) >= 5 and f[0] in ("dispatch_kernel", "dispatch_tiled_kernel", "combine_kernel"):
             out[f[0].split("_")[0]] = int(f[3]) + int(f[4])          # read bytes + written bytes
     return out
 
@@ -507,6 +507,51 @@ def main() -> int:
         step()                       # leave the buffers as the headline step leaves them
         torch.cuda.synchronize()
 
+    # where the source rows are when dispatch starts.  The timed loop above dispatches the same x every step, and
+    # dispatch's streaming stores leave x in the 256 MB memory-side cache from one step to the next.  Two more
+    # cases, per-call event times as above: a producer kernel rewrites x before every step (what a layer that has
+    # just computed x looks like), and x rotates over enough copies that no step finds its rows in the cache.
+    source_rows = None
+    if cfg.payload == "bf16" and len(sets) == 1 and not args.graph and not args.no_variants:
+        K3 = max(20, K // 4)
+        copies = max(2, -(-(512 << 20) // (cfg.N * cfg.row_bytes)) + 1)
+        d_xs = [d_x] + [d_x.clone() for _ in range(copies - 1)]
+        d_xsrc = d_x.clone()
+        nbytes3 = 2 * (cfg.N + cfg.P) * cfg.row_bytes
+
+        def source_case(before_step, x_of):
+            ev3 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K3)]
+            for row in ev3:
+                for e in row:
+                    e.record()
+            for i in range(5):
+                before_step()
+                fusco.fusco_plan(L, d_A)
+                fusco.fusco_dispatch(L, x_of(i), d_expert)
+                fusco.fusco_combine(L, d_expert, d_w, d_out)
+            torch.cuda.synchronize()
+            for i in range(K3):
+                before_step()
+                fusco.fusco_plan(L, d_A)
+                fusco.fusco_probe_time_next_call(ev3[i][0], ev3[i][1])
+                fusco.fusco_dispatch(L, x_of(i + 5), d_expert)
+                fusco.fusco_probe_time_next_call(ev3[i][2], ev3[i][3])
+                fusco.fusco_combine(L, d_expert, d_w, d_out)
+            torch.cuda.synchronize()
+            d3 = float(np.mean([ev3[i][0].elapsed_time(ev3[i][1]) for i in range(K3)]))
+            c3 = float(np.mean([ev3[i][2].elapsed_time(ev3[i][3]) for i in range(K3)]))
+            return {"steps": K3, "dispatch_ms": d3, "combine_ms": c3,
+                    "dispatch_plus_combine": {"ms": d3 + c3, "GBps": nbytes3 / ((d3 + c3) * 1e-3) / 1e9,
+                                              "frac_of_peak": nbytes3 / ((d3 + c3) * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+        source_rows = {
+            "same_x_every_step": source_case(lambda: None, lambda i: d_x),
+            "x_rewritten_before_every_step": source_case(lambda: d_x.copy_(d_xsrc), lambda i: d_x),
+            "x_rotating_over_%d_copies" % copies: source_case(lambda: None, lambda i: d_xs[i % copies]),
+        }
+        del d_xs, d_xsrc
+        step()
+        torch.cuda.synchronize()
+
     variants = None
     if not args.no_variants and cfg.payload == "bf16":
         variants = time_variants(fusco, torch, cfg, L, d_A, d_x, d_w, d_expert, d_out, max(10, K // 4))
@@ -623,6 +668,8 @@ def main() -> int:
     }
     if own_y is not None:
         result["expert_output_in_own_buffer"] = own_y
+    if source_rows is not None:
+        result["source_rows"] = source_rows
     if fused is not None:
         result["fused_plan_dispatch_step"] = fused
     if ceilings is not None:
