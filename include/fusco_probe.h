@@ -69,6 +69,16 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
                                const uint32_t *d_slice_fill, uint32_t max_polls, uint32_t *d_report, void *stream);
 
 /*
+ * Study and test aid: the largest source tensor (bytes of x plus its second plane) that fusco_dispatch's
+ * tiled mode takes in one piece.  Larger ones are taken in chunks of whole rounds of 8 tiles whose source rows
+ * fit this many bytes (at least 8 tiles), each chunk with launches of its own: a sequential read of the chunk's
+ * source rows, which leaves them in the 256 MB memory-side cache, then the chunk's tiles.  bytes = 0 only
+ * reads the value; otherwise the value is replaced, for the whole process, and the previous one returned.
+ * The default is 128 MiB.  The result of fusco_dispatch does not depend on it.
+ */
+size_t fusco_probe_source_chunk_bytes(size_t bytes);
+
+/*
  * Measurement aid: kernel time without stream events between the kernels.  The next fusco_plan,
  * fusco_dispatch (fused modes), fusco_plan_dispatch or fusco_combine call made by the calling thread attaches the two HIP
  * events (hipEvent_t passed as void*, created with timing enabled) to its own kernels: start_event

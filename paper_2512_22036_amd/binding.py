@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.fusco_probe_source_chunk_bytes.restype = ctypes.c_size_t
+    lib.fusco_probe_source_chunk_bytes.argtypes = [sz]
     lib.fusco_probe_time_next_call.restype = ctypes.c_int
     lib.fusco_probe_time_next_call.argtypes = [vp, vp]
     lib.fusco_probe_rows.restype = ctypes.c_int
@@ -380,6 +382,12 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
         raise FuscoError("dst is smaller than src")
     _check(load_library().fusco_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)),
            "fusco_probe_copy")
+
+
+def fusco_probe_source_chunk_bytes(nbytes: int = 0) -> int:
+    """Largest source tensor the tiled dispatch takes in one piece; a non-zero value replaces it (returns the
+    previous one)."""
+    return int(load_library().fusco_probe_source_chunk_bytes(int(nbytes)))
 
 
 def fusco_probe_time_next_call(start: torch.cuda.Event, stop: torch.cuda.Event) -> None:

@@ -11,6 +11,7 @@
 // One translation unit: the kernels live in the headers next to this file (planner.h, movers.h,
 // segments.h, probes.h), the host-side helpers in launch.h, the C entry points below.
 #include "launch.h"
+#include <atomic>
 #include <mutex>
 
 extern "C" {
@@ -218,6 +219,9 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     return launch_status();
 }
 
+// largest source tensor that the tiled dispatch takes in one piece (fusco_probe_source_chunk_bytes changes it)
+static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
+
 // the conditions under which fusco_dispatch moves the rows tile by tile in transfer order
 static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
                                        bool wire, bool two_hop)
@@ -286,20 +290,44 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     if (dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, expert, wire, two_hop)) {
         a.slot_token = L->slot_token; a.tile_slots = L->tile_slots;
         a.tile_cap = L->tile_tokens * L->k; a.n_tiles = L->tile_count;
-        const unsigned rounds_of_tiles = (unsigned)((L->tile_count + kXcds - 1) / kXcds);
-        const dim3 tgrid(rounds_of_tiles * (unsigned)a.tile_cap * kXcds, (unsigned)segs), tblock((unsigned)threads);
-        if (a.Ca) {
-            switch (cpt) {
-            case 1: launch(dispatch_tiled_kernel<1, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-            case 2: launch(dispatch_tiled_kernel<2, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-            default: launch(dispatch_tiled_kernel<4, true>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+        // a source tensor that cannot stay in the memory-side cache is taken in chunks of whole rounds of tiles
+        // whose rows fit half of it, every chunk after a sequential read of its source rows (touch_kernel)
+        const size_t source_bytes = (size_t)L->N * (row_bytes + aux_row_bytes);
+        const size_t chunk_limit = g_source_chunk_bytes.load(std::memory_order_relaxed);
+        size_t chunk_tiles = (size_t)L->tile_count;
+        const bool chunked = source_bytes > chunk_limit;
+        if (chunked) {
+            chunk_tiles = chunk_limit / ((size_t)L->tile_tokens * (row_bytes + aux_row_bytes)) / kXcds * kXcds;
+            if (chunk_tiles < (size_t)kXcds) chunk_tiles = kXcds;
+        }
+        const dim3 tblock((unsigned)threads);
+        for (size_t tile0 = 0; tile0 < (size_t)L->tile_count; tile0 += chunk_tiles) {
+            const size_t tiles_here = std::min(chunk_tiles, (size_t)L->tile_count - tile0);
+            const bool first = tile0 == 0, last = tile0 + tiles_here == (size_t)L->tile_count;
+            if (chunked) {
+                const size_t t0 = tile0 * (size_t)L->tile_tokens;
+                const size_t rows = std::min(tiles_here * (size_t)L->tile_tokens, (size_t)L->N - t0);
+                const size_t n = rows * (size_t)a.C, na = rows * (size_t)a.Ca;
+                launch_args(touch_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), s, first ? ev.start : nullptr, (hipEvent_t) nullptr,
+                       a.x + t0 * (size_t)a.C, n);
+                if (na)
+                    launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
+                           a.x_aux + t0 * (size_t)a.Ca, na);
             }
-        } else {
+            const dim3 tgrid((unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * kXcds, (unsigned)segs);
+            hipEvent_t e0 = first && !chunked ? ev.start : nullptr, e1 = last ? ev.stop : nullptr;
+            const uint32_t tb = (uint32_t)tile0, th = (uint32_t)tiles_here;
+#define FUSCO_TILED(CPT)                                                                              \
+    do {                                                                                              \
+        if (a.Ca) launch_args(dispatch_tiled_kernel<CPT, true>, tgrid, tblock, s, e0, e1, a, tb, th); \
+        else launch_args(dispatch_tiled_kernel<CPT, false>, tgrid, tblock, s, e0, e1, a, tb, th);     \
+    } while (0)
             switch (cpt) {
-            case 1: launch(dispatch_tiled_kernel<1, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-            case 2: launch(dispatch_tiled_kernel<2, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
-            default: launch(dispatch_tiled_kernel<4, false>, tgrid, tblock, s, a, ev.start, ev.stop); break;
+            case 1: FUSCO_TILED(1); break;
+            case 2: FUSCO_TILED(2); break;
+            default: FUSCO_TILED(4); break;
             }
+#undef FUSCO_TILED
         }
         return launch_status();
     }
@@ -598,6 +626,11 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
     a.n_slices = (uint32_t)slices; a.max_polls = max_polls; a.report = d_report;
     hipLaunchKernelGGL(consume_slices_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, a);
     return launch_status();
+}
+
+size_t fusco_probe_source_chunk_bytes(size_t bytes)
+{
+    return bytes ? g_source_chunk_bytes.exchange(bytes) : g_source_chunk_bytes.load();
 }
 
 int fusco_probe_time_next_call(void *start_event, void *stop_event)

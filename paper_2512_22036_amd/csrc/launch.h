@@ -54,6 +54,14 @@ void launch(K kernel, dim3 grid, dim3 block, hipStream_t s, const A &a, hipEvent
     else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
 }
 
+// the same for kernels with several arguments
+template <typename K, typename... A>
+void launch_args(K kernel, dim3 grid, dim3 block, hipStream_t s, hipEvent_t e0, hipEvent_t e1, A... args)
+{
+    if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+}
+
 template <bool Y_BF16, bool OUT_BF16>
 void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {

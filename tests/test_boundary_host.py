@@ -232,6 +232,11 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_copy(buf, buf + 4096, 0, None) == 0
     assert lib.fusco_probe_time_next_call(None, buf) == -1 and lib.fusco_probe_time_next_call(buf, None) == -1
     # probe pieces
+    lib.fusco_probe_source_chunk_bytes.restype = ctypes.c_size_t
+    lib.fusco_probe_source_chunk_bytes.argtypes = [ctypes.c_size_t]
+    assert lib.fusco_probe_source_chunk_bytes(0) == 128 << 20              # reading leaves the value alone
+    assert lib.fusco_probe_source_chunk_bytes(1 << 20) == 128 << 20 and lib.fusco_probe_source_chunk_bytes(0) == 1 << 20
+    assert lib.fusco_probe_source_chunk_bytes(128 << 20) == 1 << 20
     pp = lib.fusco_probe_pieces
     assert pp(None, 1 << 20, 1, 1, 0, None, None) == -1
     assert pp(buf, (1 << 20) + 16, 1, 1, 0, None, None) == -1              # not whole pieces

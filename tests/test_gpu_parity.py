@@ -631,6 +631,39 @@ def test_dispatch_in_transfer_order_matches_oracle(fusco, oracle, N, k, E, D, ro
     assert torch.equal(eb2, eb) and (not aux_bytes or torch.equal(ea2, ea))
 
 
+@pytest.mark.parametrize("chunk_tiles", [8, 16])
+@pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", TILED_SHAPES)
+def test_dispatch_in_source_chunks_matches_oracle(fusco, oracle, chunk_tiles, N, k, E, D, row_bytes, aux_bytes, distinct):
+    """Source tensors larger than the memory-side cache are moved in chunks of tiles, every chunk starting with a read
+    of its source rows.  The chunk size is lowered here so that small inputs take that path: 8 tiles (the smallest,
+    a last chunk with fewer tiles than XCDs for the 17- and 35-tile inputs) and 16 tiles."""
+    rng = np.random.default_rng(N + row_bytes + chunk_tiles)
+    A = random_topk(rng, N, k, E, distinct)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    xa = rng.integers(0, 256, size=(N, aux_bytes), dtype=np.uint8) if aux_bytes else None
+    want = oracle.plan(A, E, D)
+    L, got = gpu_plan(fusco, A, E, D)
+    assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes, aux_bytes)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    ea = torch.full((L.P, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda") if aux_bytes else None
+    limit = chunk_tiles * L.tile_tokens * (row_bytes + aux_bytes)
+    assert N * (row_bytes + aux_bytes) > limit                      # several chunks
+    before = fusco.fusco_probe_source_chunk_bytes(limit)
+    try:
+        assert fusco.fusco_probe_source_chunk_bytes() == limit
+        fusco.fusco_dispatch(L, dev(x), eb, x_aux=dev(xa) if aux_bytes else None, expert_aux=ea)
+        torch.cuda.synchronize()
+    finally:
+        fusco.fusco_probe_source_chunk_bytes(before)
+    assert fusco.fusco_probe_source_chunk_bytes() == before == 128 << 20
+    if aux_bytes:
+        _, expert_want, _, eaux_want = oracle.dispatch(want, x, xa)
+        assert np.array_equal(ea.cpu().numpy(), eaux_want)
+    else:
+        _, expert_want = oracle.dispatch(want, x)
+    assert np.array_equal(eb.cpu().numpy(), expert_want)
+
+
 def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle):
     rng = np.random.default_rng(5)
     N, k, E, D, row_bytes = 5000, 8, 64, 8, 1024
