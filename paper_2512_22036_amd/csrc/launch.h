@@ -115,7 +115,9 @@ int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_
 // still holds the rows written for the last tokens.  Measured on MI355X (8192 tokens x 8 rows of 14 KiB): a
 // walk that starts about 110-220 MiB of rows before the end, goes up to the last token and then wraps to
 // token 0 is 7 us (2 %) faster than a walk from the last token down, and 25 us faster than one from token 0
-// up.  When y comes from somewhere else the order makes no difference.
+// up.  That holds after a dispatch that writes with plain stores (the token walk); the tiled dispatch's
+// streaming stores leave nothing in that cache, and when y comes from somewhere else the order makes no
+// difference either.
 constexpr size_t kRecentRowBytes = (size_t)160 << 20;
 
 int combine_first_row(int N, int k, size_t row_bytes)
