@@ -511,7 +511,7 @@ def main() -> int:
     # dispatch's streaming stores leave x in the 256 MB memory-side cache from one step to the next.  Two more
     # cases, per-call event times as above: a producer kernel rewrites x before every step (what a layer that has
     # just computed x looks like), and x rotates over enough copies that no step finds its rows in the cache.
-    source_rows = None
+    source_rows = token_walk = None
     if cfg.payload == "bf16" and len(sets) == 1 and not args.graph and not args.no_variants:
         K3 = max(20, K // 4)
         copies = max(2, -(-(512 << 20) // (cfg.N * cfg.row_bytes)) + 1)
@@ -543,6 +543,14 @@ def main() -> int:
             return {"steps": K3, "dispatch_ms": d3, "combine_ms": c3,
                     "dispatch_plus_combine": {"ms": d3 + c3, "GBps": nbytes3 / ((d3 + c3) * 1e-3) / 1e9,
                                               "frac_of_peak": nbytes3 / ((d3 + c3) * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+        # the same step with fusco_dispatch kept on the token walk (one workgroup per token), when the library would
+        # move the rows tile by tile in transfer order: what the transfer order is worth, in one run
+        if fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes, 0):
+            fusco.fusco_probe_dispatch_token_walk(1)
+            try:
+                token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x)}
+            finally:
+                fusco.fusco_probe_dispatch_token_walk(0)
         source_rows = {
             "same_x_every_step": source_case(lambda: None, lambda i: d_x),
             "x_rewritten_before_every_step": source_case(lambda: d_x.copy_(d_xsrc), lambda i: d_x),
@@ -670,6 +678,8 @@ def main() -> int:
         result["expert_output_in_own_buffer"] = own_y
     if source_rows is not None:
         result["source_rows"] = source_rows
+    if token_walk is not None:
+        result["dispatch_kept_on_token_walk"] = token_walk
     if fused is not None:
         result["fused_plan_dispatch_step"] = fused
     if ceilings is not None:

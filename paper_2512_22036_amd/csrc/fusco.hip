@@ -222,11 +222,15 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
 // largest source tensor that the tiled dispatch takes in one piece (fusco_probe_source_chunk_bytes changes it)
 static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
 
+// fusco_probe_dispatch_token_walk: non-zero keeps fusco_dispatch on the token walk (for comparisons)
+static std::atomic<int> g_force_token_walk{0};
+
 // the conditions under which fusco_dispatch moves the rows tile by tile in transfer order
 static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
                                        bool wire, bool two_hop)
 {
     const size_t tile_source_bytes = (size_t)L->tile_tokens * (row_bytes + aux_row_bytes);
+    if (g_force_token_walk.load(std::memory_order_relaxed)) return false;
     return expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
            tile_source_bytes <= kTiledMaxTileBytes;
 }
@@ -626,6 +630,11 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
     a.n_slices = (uint32_t)slices; a.max_polls = max_polls; a.report = d_report;
     hipLaunchKernelGGL(consume_slices_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, a);
     return launch_status();
+}
+
+int fusco_probe_dispatch_token_walk(int on)
+{
+    return on < 0 ? g_force_token_walk.load() : g_force_token_walk.exchange(on ? 1 : 0);
 }
 
 size_t fusco_probe_source_chunk_bytes(size_t bytes)

@@ -698,3 +698,25 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
     assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
     assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_STREAMING)
     assert not fusco.fusco_dispatch_in_transfer_order(top1, 2048)
+
+
+def test_dispatch_kept_on_the_token_walk_gives_the_same_rows(fusco, oracle):
+    """The study knob that keeps fusco_dispatch on the token walk changes the kernel, not the result."""
+    rng = np.random.default_rng(77)
+    N, k, E, D, row_bytes = 4500, 8, 64, 8, 1024
+    A = random_topk(rng, N, k, E)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    want = oracle.plan(A, E, D)
+    L, got = gpu_plan(fusco, A, E, D)
+    assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    assert fusco.fusco_probe_dispatch_token_walk(1) == 0
+    try:
+        assert not fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+        fusco.fusco_dispatch(L, dev(x), eb)
+        torch.cuda.synchronize()
+    finally:
+        fusco.fusco_probe_dispatch_token_walk(0)
+    assert fusco.fusco_probe_dispatch_token_walk() == 0 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+    _, expert_want = oracle.dispatch(want, x)
+    assert np.array_equal(eb.cpu().numpy(), expert_want)
