@@ -153,8 +153,10 @@ int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
  *     send_buf[pair_send_row[t*k+j]] = x[t] where pair_first       (FUSCO_DISPATCH_WIRE)
  * For large inputs the expert tensor is written tile by tile in the layout's transfer order (see
  * fusco_dispatch_in_transfer_order): every XCD of the GPU takes whole tiles of tokens and writes their rows
- * expert by expert with streaming stores, the tile's source rows being read from HBM once and from the XCD's
- * L2 afterwards.  Otherwise every token's row is read once and stored to its k rows at once.
+ * expert by expert with streaming stores, the tile's source rows being read from memory once and from the
+ * XCD's L2 afterwards while they stay there.  A source tensor of more than 128 MiB is taken in chunks of tiles,
+ * each chunk after a sequential read of its source rows (a few launches instead of one).  Otherwise every
+ * token's row is read once and stored to its k rows at once (token walk).
  * Rows are opaque bytes.  d_x: [N, row_bytes], row_bytes a positive multiple of 16.  An optional
  * second plane (e.g. per-block scales of an fp8 payload) of aux_row_bytes (multiple of 16, or 0
  * with NULL aux pointers) follows the same descriptors; row_bytes + aux_row_bytes may not exceed
@@ -167,12 +169,11 @@ int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
  *     expert_buf[s] = send_buf[slot_send_row[s]]
  * for every assigned slot.  Both tensors are written and hold the same bytes as in the fused mode;
  * the extra pass costs U + P more row reads.
- * FUSCO_DISPATCH_STREAMING may be added to the fused modes (not to FUSCO_DISPATCH_TWO_HOP): the same rows are
- * written with non-temporal stores, which do not stay in the GPU's 256 MB memory-side cache.  Choose it when
- * other traffic (an expert computation) comes between this call and the first reader of the rows: a plain
- * dispatch leaves its last ~200 MB of rows dirty in that cache, and whoever streams through memory next pays
- * for writing them back.  Leave it out when fusco_combine (or any reader) follows at once on these rows: they
- * are then read from the cache.  Results are identical either way.
+ * FUSCO_DISPATCH_STREAMING may be added to the fused modes (not to FUSCO_DISPATCH_TWO_HOP): the token walk then
+ * writes its rows with non-temporal stores, which do not stay in the GPU's 256 MB memory-side cache (the
+ * transfer order always writes that way).  Choose it when other traffic (an expert computation) comes between
+ * this call and the first reader of the rows: a plain dispatch leaves its last ~200 MB of rows dirty in that
+ * cache, and whoever streams through memory next pays for writing them back.  Results are identical either way.
  */
 int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,
