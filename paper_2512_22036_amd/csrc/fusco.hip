@@ -202,7 +202,7 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
     m.send_buf = nullptr; m.send_aux = nullptr;
     m.pair_slot = L->pair_slot; m.pair_send_row = L->pair_send_row; m.pair_first = L->pair_first;
-    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0; m.n_tiles = 0;
+    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0;
     m.k = L->k;
     m.C = (int32_t)(row_bytes / 16); m.Ca = (int32_t)(aux_row_bytes / 16);
     m.write_expert = 1; m.write_wire = 0;
@@ -274,7 +274,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.expert_buf = (u32x4 *)d_expert_buf; a.expert_aux = (u32x4 *)d_expert_aux;
     a.send_buf = (u32x4 *)d_send_buf; a.send_aux = (u32x4 *)d_send_aux;
     a.pair_slot = L->pair_slot; a.pair_send_row = L->pair_send_row; a.pair_first = L->pair_first;
-    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0; a.n_tiles = 0;
+    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0;
     a.k = L->k;
     a.C = (int32_t)(row_bytes / 16);
     a.Ca = (int32_t)(aux_row_bytes / 16);
@@ -293,7 +293,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     // in one XCD's 4 MB L2: the rows are moved tile by tile in transfer order (dispatch_tiled_kernel).
     if (dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, expert, wire, two_hop)) {
         a.slot_token = L->slot_token; a.tile_slots = L->tile_slots;
-        a.tile_cap = L->tile_tokens * L->k; a.n_tiles = L->tile_count;
+        a.tile_cap = L->tile_tokens * L->k;
         // a source tensor that cannot stay in the memory-side cache is taken in chunks of whole rounds of tiles
         // whose rows fit half of it, every chunk after a sequential read of its source rows (touch_kernel)
         const size_t source_bytes = (size_t)L->N * (row_bytes + aux_row_bytes);

@@ -8,11 +8,12 @@
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// Movers.  Both give one workgroup to one token, because HBM rewards long bursts: a row is
-// fetched or written whole by neighbouring waves of one compute unit within a short time.
-// Measured on MI355X at 14 KiB rows: scattered row reads reach the streaming read rate, scattered
-// row writes do not (about 5.2 of 6.9 TB/s), so the movers keep the scattered side of dispatch
-// as short as possible (plain cached stores, several chunks per thread in flight).
+// Movers.  A row is fetched or written whole by the waves of one workgroup within a short time.
+// Measured on MI355X at 14 KiB rows: scattered row reads come close to the streaming read rate
+// (6.4-6.6 of 7.2 TB/s), scattered row writes do not (5.2-5.4 of 6.9 TB/s), and what the write
+// rate depends on is which XCD writes which neighbouring addresses.  Combine therefore walks the
+// tokens (its scattered side is the reads), and dispatch writes in the planner's transfer order
+// where it can (dispatch_tiled_kernel) and walks the tokens otherwise (dispatch_kernel).
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ u32x4 load16_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 
@@ -44,7 +45,7 @@ struct DispatchArgs {
     const int32_t *pair_slot, *pair_send_row;
     const uint8_t *pair_first;
     const int32_t *slot_token, *tile_slots;   // tiled mode: transfer order of every tile
-    int32_t tile_cap, n_tiles;                // entries per tile in tile_slots, number of tiles
+    int32_t tile_cap;                         // entries per tile in tile_slots
     int32_t k;
     int32_t C, Ca;   // 16-byte chunks per row in the main and in the aux plane
     int32_t write_expert, write_wire;
@@ -56,9 +57,9 @@ constexpr size_t kTiledMaxTileBytes = (size_t)3840 << 10; // source rows of one 
 constexpr size_t kSourceChunkBytes = (size_t)128 << 20;   // source rows of one chunk: half the 256 MB memory-side cache
 
 // STREAM: the rows are written with non-temporal stores, which go past the memory-side cache (measured: a
-// read that follows such a write runs at the cold rate, 6.2 TB/s for 256 MB, instead of 4.1 TB/s on rows
-// that sit dirty in that cache).  Right when the rows are not read back soon; slower when they are.
-template <int CPT, bool STREAM>
+// read that follows such a write runs at the cold rate, 5.7 TB/s for 256 MB, instead of 4.2 TB/s on rows
+// that sit dirty in that cache).
+template <bool STREAM>
 __device__ __forceinline__ void put16(u32x4 *p, u32x4 v)
 {
     if constexpr (STREAM) __builtin_nontemporal_store(v, p);
@@ -86,8 +87,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) put16<CPT, STREAM>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
-                else if (c < Ct) put16<CPT, STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
+                if (c < a.C) put16<STREAM>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
+                else if (c < Ct) put16<STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -100,8 +101,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
-                if (c < a.C) put16<CPT, STREAM>(a.send_buf + (size_t)row * a.C + c, v[i]);
-                else if (c < Ct) put16<CPT, STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
+                if (c < a.C) put16<STREAM>(a.send_buf + (size_t)row * a.C + c, v[i]);
+                else if (c < Ct) put16<STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(256) void dispatch_tiled_kernel(DispatchArgs a, uin
 }
 
 // Reads n 16-byte units once, 4 KiB per workgroup in address order, and drops them: afterwards they sit in the
-// memory-side cache.  The tiled dispatch of a source tensor larger than that cache runs it over the source rows
+// memory-side cache.  The tiled dispatch of a source tensor larger than half that cache runs it over the source rows
 // of the next chunk of tiles, so that they reach memory as one sequential burst of reads, with no writes in
 // flight, instead of trickling out between the writes (measured at 32 Ki tokens of 14 KiB, chunks of 32 tiles:
 // 760 us instead of 824 us; as part of the tiled kernel's own launch the reads did not help).
