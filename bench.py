@@ -546,17 +546,26 @@ def main() -> int:
         # the same step with fusco_dispatch kept on the token walk (one workgroup per token), when the library would
         # move the rows tile by tile in transfer order: what the transfer order is worth, in one run
         if fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes, 0):
-            fusco.fusco_probe_dispatch_token_walk(1)
             try:
+                fusco.fusco_probe_dispatch_kernel(1)
                 token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x)}
             finally:
-                fusco.fusco_probe_dispatch_token_walk(0)
+                fusco.fusco_probe_dispatch_kernel(0)
+        # a layer's other traffic between two shuffles (weights, attention) leaves nothing of the previous step in the
+        # memory-side cache: 1 GiB of another buffer is read before x is rewritten
+        d_other = torch.empty((1 << 30) // 16384, 16384, dtype=torch.uint8, device="cuda")
+        d_sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+        def other_traffic_then_x():
+            fusco.fusco_probe_rows(d_other, None, 1, 0, False, sink=d_sink)
+            d_x.copy_(d_xsrc)
         source_rows = {
             "same_x_every_step": source_case(lambda: None, lambda i: d_x),
             "x_rewritten_before_every_step": source_case(lambda: d_x.copy_(d_xsrc), lambda i: d_x),
+            "1GiB_of_other_reads_then_x_rewritten_before_every_step": source_case(other_traffic_then_x, lambda i: d_x),
             "x_rotating_over_%d_copies" % copies: source_case(lambda: None, lambda i: d_xs[i % copies]),
         }
-        del d_xs, d_xsrc
+        del d_xs, d_xsrc, d_other
         step()
         torch.cuda.synchronize()
 

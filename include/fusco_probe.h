@@ -69,12 +69,12 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
                                const uint32_t *d_slice_fill, uint32_t max_polls, uint32_t *d_report, void *stream);
 
 /*
- * Study aid: on != 0 keeps every later fusco_dispatch of the process on the token walk (one workgroup per token),
- * also where it would move the rows tile by tile in transfer order; on == 0 restores the automatic choice;
- * on < 0 only reads the setting.  Returns the previous setting.  fusco_dispatch_in_transfer_order reflects it.
- * The result of fusco_dispatch does not depend on it.
+ * Study aid: which kernel every later fusco_dispatch of the process uses where it has a choice.  0: automatic.
+ * 1: the token walk (one workgroup per token), also where the rows would be moved tile by tile in transfer
+ * order; fusco_dispatch_in_transfer_order reflects it.  which < 0 only reads the setting.  Returns the previous
+ * setting, FUSCO_ERR_INVALID_ARG for which > 1.  The result of fusco_dispatch does not depend on it.
  */
-int fusco_probe_dispatch_token_walk(int on);
+int fusco_probe_dispatch_kernel(int which);
 
 /*
  * Study and test aid: the largest source tensor (bytes of x plus its second plane) that fusco_dispatch's

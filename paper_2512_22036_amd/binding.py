@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_token_walk",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_kernel",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -84,8 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_combine.argtypes = [ctypes.POINTER(_CLayout), vp, ctypes.c_int, vp, vp, ctypes.c_int, i32, u32, vp]
     lib.fusco_probe_copy.restype = ctypes.c_int
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
-    lib.fusco_probe_dispatch_token_walk.restype = ctypes.c_int
-    lib.fusco_probe_dispatch_token_walk.argtypes = [ctypes.c_int]
+    lib.fusco_probe_dispatch_kernel.restype = ctypes.c_int
+    lib.fusco_probe_dispatch_kernel.argtypes = [ctypes.c_int]
     lib.fusco_probe_source_chunk_bytes.restype = ctypes.c_size_t
     lib.fusco_probe_source_chunk_bytes.argtypes = [sz]
     lib.fusco_probe_time_next_call.restype = ctypes.c_int
@@ -386,10 +386,13 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
            "fusco_probe_copy")
 
 
-def fusco_probe_dispatch_token_walk(on: int = -1) -> int:
-    """Keeps fusco_dispatch on the token walk (on != 0), restores the automatic choice (0) or reads the setting (< 0);
-    returns the previous setting."""
-    return int(load_library().fusco_probe_dispatch_token_walk(int(on)))
+def fusco_probe_dispatch_kernel(which: int = -1) -> int:
+    """Which kernel fusco_dispatch uses where it has a choice: 0 automatic, 1 token walk; < 0 reads the setting.
+    Returns the previous setting."""
+    rc = int(load_library().fusco_probe_dispatch_kernel(int(which)))
+    if rc < 0:
+        _check(rc, "fusco_probe_dispatch_kernel")
+    return rc
 
 
 def fusco_probe_source_chunk_bytes(nbytes: int = 0) -> int:

@@ -222,15 +222,15 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
 // largest source tensor that the tiled dispatch takes in one piece (fusco_probe_source_chunk_bytes changes it)
 static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
 
-// fusco_probe_dispatch_token_walk: non-zero keeps fusco_dispatch on the token walk (for comparisons)
-static std::atomic<int> g_force_token_walk{0};
+// fusco_probe_dispatch_kernel: 0 automatic; 1 keeps fusco_dispatch on the token walk (for comparisons)
+static std::atomic<int> g_dispatch_kernel{0};
 
 // the conditions under which fusco_dispatch moves the rows tile by tile in transfer order
 static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
                                        bool wire, bool two_hop)
 {
     const size_t tile_source_bytes = (size_t)L->tile_tokens * (row_bytes + aux_row_bytes);
-    if (g_force_token_walk.load(std::memory_order_relaxed)) return false;
+    if (g_dispatch_kernel.load(std::memory_order_relaxed) == 1) return false;
     return expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
            tile_source_bytes <= kTiledMaxTileBytes;
 }
@@ -318,9 +318,10 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                     launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
                            a.x_aux + t0 * (size_t)a.Ca, na);
             }
-            const dim3 tgrid((unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * kXcds, (unsigned)segs);
+            const unsigned tblocks = (unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * kXcds;
             hipEvent_t e0 = first && !chunked ? ev.start : nullptr, e1 = last ? ev.stop : nullptr;
             const uint32_t tb = (uint32_t)tile0, th = (uint32_t)tiles_here;
+            const dim3 tgrid(tblocks, (unsigned)segs);
 #define FUSCO_TILED(CPT)                                                                              \
     do {                                                                                              \
         if (a.Ca) launch_args(dispatch_tiled_kernel<CPT, true>, tgrid, tblock, s, e0, e1, a, tb, th); \
@@ -632,9 +633,10 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
     return launch_status();
 }
 
-int fusco_probe_dispatch_token_walk(int on)
+int fusco_probe_dispatch_kernel(int which)
 {
-    return on < 0 ? g_force_token_walk.load() : g_force_token_walk.exchange(on ? 1 : 0);
+    if (which > 1) return FUSCO_ERR_INVALID_ARG;
+    return which < 0 ? g_dispatch_kernel.load() : g_dispatch_kernel.exchange(which);
 }
 
 size_t fusco_probe_source_chunk_bytes(size_t bytes)

@@ -595,6 +595,12 @@ TILED_SHAPES = [
     (5000, 8, 256, 8, 14336, 224, True),      # the benchmark's rows plus a plane of scales: 3.7 MB of source per tile
     (6000, 6, 10, 5, 256, 0, False),          # repeated experts inside a token
     (8192, 8, 256, 8, 4096, 0, True),         # exactly 32 full tiles
+    # rows of 4 KiB and more that are not multiples of 4 KiB
+    (4100, 8, 32, 8, 6144, 0, True),          # one and a half pieces per row, long runs (32 experts)
+    (4200, 8, 256, 8, 5008, 48, True),        # an odd number of 16-byte units per row, short runs, a second plane
+    (2100, 16, 64, 8, 18448, 0, True),        # 1153 units: two workgroup columns; 128 tokens per tile
+    (1100, 32, 64, 8, 41008, 16, True),       # 2563 units: three workgroup columns; 64 tokens per tile
+    (6000, 6, 10, 5, 4112, 0, False),         # repeated experts inside a token: neighbouring slots from one token
 ]
 
 
@@ -710,13 +716,13 @@ def test_dispatch_kept_on_the_token_walk_gives_the_same_rows(fusco, oracle):
     L, got = gpu_plan(fusco, A, E, D)
     assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
     eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
-    assert fusco.fusco_probe_dispatch_token_walk(1) == 0
+    assert fusco.fusco_probe_dispatch_kernel(1) == 0
     try:
         assert not fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
         fusco.fusco_dispatch(L, dev(x), eb)
         torch.cuda.synchronize()
     finally:
-        fusco.fusco_probe_dispatch_token_walk(0)
-    assert fusco.fusco_probe_dispatch_token_walk() == 0 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+        fusco.fusco_probe_dispatch_kernel(0)
+    assert fusco.fusco_probe_dispatch_kernel() == 0 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
     _, expert_want = oracle.dispatch(want, x)
     assert np.array_equal(eb.cpu().numpy(), expert_want)
