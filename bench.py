@@ -519,7 +519,7 @@ def main() -> int:
         d_xsrc = d_x.clone()
         nbytes3 = 2 * (cfg.N + cfg.P) * cfg.row_bytes
 
-        def source_case(before_step, x_of):
+        def source_case(before_step, x_of, flags=0):
             ev3 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K3)]
             for row in ev3:
                 for e in row:
@@ -527,14 +527,14 @@ def main() -> int:
             for i in range(5):
                 before_step()
                 fusco.fusco_plan(L, d_A)
-                fusco.fusco_dispatch(L, x_of(i), d_expert)
+                fusco.fusco_dispatch(L, x_of(i), d_expert, flags=flags)
                 fusco.fusco_combine(L, d_expert, d_w, d_out)
             torch.cuda.synchronize()
             for i in range(K3):
                 before_step()
                 fusco.fusco_plan(L, d_A)
                 fusco.fusco_probe_time_next_call(ev3[i][0], ev3[i][1])
-                fusco.fusco_dispatch(L, x_of(i + 5), d_expert)
+                fusco.fusco_dispatch(L, x_of(i + 5), d_expert, flags=flags)
                 fusco.fusco_probe_time_next_call(ev3[i][2], ev3[i][3])
                 fusco.fusco_combine(L, d_expert, d_w, d_out)
             torch.cuda.synchronize()
@@ -548,7 +548,8 @@ def main() -> int:
         if fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes, 0):
             try:
                 fusco.fusco_probe_dispatch_kernel(1)
-                token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x)}
+                token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x),
+                              "streaming_stores": source_case(lambda: None, lambda i: d_x, fusco.DISPATCH_STREAMING)}
             finally:
                 fusco.fusco_probe_dispatch_kernel(0)
         # a layer's other traffic between two shuffles (weights, attention) leaves nothing of the previous step in the
