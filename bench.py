@@ -303,6 +303,48 @@ def plan_scaling(fusco, torch, reps=20):
     return {"k": 8, "E": 256, "D": 8, "reps": reps, "sizes": out}
 
 
+def row_sweep(fusco, torch, np, W, reps=30):
+    """Dispatch and combine over the hidden size, at the dsv3 workload's routing (8192 tokens, top-8 of 256 experts,
+    bf16 rows of 2 * hidden bytes), per-call kernel times as in the benchmark line.  x larger than 128 MiB is
+    dispatched in source chunks; rows longer than 15 KiB are moved in column segments."""
+    cfg = W.get_config("dsv3")
+    A, w = W.make_routing(cfg)
+    d_A, d_w = torch.from_numpy(A).cuda(), torch.from_numpy(w).cuda()
+    L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+    fusco.fusco_plan(L, d_A)
+    torch.cuda.synchronize()
+    first = L.array("pair_slot").long()[::cfg.k][:64]
+    rows = []
+    for H in (2048, 4096, 6144, 7168, 7680, 7936, 8192, 10240, 12288, 16384, 24576):
+        x = torch.randn((cfg.N, H), device="cuda").to(torch.bfloat16)
+        eb = torch.empty((cfg.P, H), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty((cfg.N, H), dtype=torch.bfloat16, device="cuda")
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
+        for r in ev:
+            for e in r:
+                e.record()
+        for _ in range(5):
+            fusco.fusco_dispatch(L, x, eb)
+            fusco.fusco_combine(L, eb, d_w, out)
+        torch.cuda.synchronize()
+        for i in range(reps):
+            fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
+            fusco.fusco_dispatch(L, x, eb)
+            fusco.fusco_probe_time_next_call(ev[i][2], ev[i][3])
+            fusco.fusco_combine(L, eb, d_w, out)
+        torch.cuda.synchronize()
+        if not torch.equal(eb[first], x[:64]):
+            raise RuntimeError("row sweep: dispatch moved wrong rows at hidden %d" % H)
+        d = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(reps)])) * 1e3
+        c = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(reps)])) * 1e3
+        nb = (cfg.N + cfg.P) * H * 2
+        rows.append({"hidden": H, "row_bytes": H * 2, "transfer_order": bool(fusco.fusco_dispatch_in_transfer_order(L, H * 2)),
+                     "dispatch_us": d, "dispatch_GBps": nb / d / 1e3, "combine_us": c, "combine_GBps": nb / c / 1e3,
+                     "frac_of_peak": 2 * nb / ((d + c) * 1e-6) / 1e9 / HBM_PEAK_GBS})
+        del x, eb, out
+    return {"N": cfg.N, "k": cfg.k, "E": cfg.E, "reps": reps, "sizes": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -328,6 +370,8 @@ def main() -> int:
                          "right after a read and right after a write of it")
     ap.add_argument("--plan-scaling", action="store_true",
                     help="instead of the benchmark line, print fusco_plan's time for 8 Ki to 2 Mi tokens")
+    ap.add_argument("--row-sweep", action="store_true",
+                    help="instead of the benchmark line, print dispatch and combine times for hidden sizes 2048 ... 24576")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -350,6 +394,9 @@ def main() -> int:
     cfg = W.get_config(args.config)
     if args.cache_probe:
         print(json.dumps({"cache_probe": cache_probe(fusco, torch, cfg.row_bytes)}))
+        return 0
+    if args.row_sweep:
+        print(json.dumps({"row_sweep": row_sweep(fusco, torch, np, W)}))
         return 0
     if args.plan_scaling:
         print(json.dumps({"plan_scaling": plan_scaling(fusco, torch)}))

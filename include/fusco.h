@@ -182,9 +182,10 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
 /*
  * Host-only: 1 if fusco_dispatch with these row sizes and flags moves the rows tile by tile in the layout's
  * transfer order (tile_slots), 0 if it walks the tokens, negative on invalid arguments.  The transfer order
- * is used when only the expert tensor is written, k >= 2, the layout has at least 16 tiles and the source
- * rows of one tile (tile_tokens * (row_bytes + aux_row_bytes)) fit the 4 MB L2 of an XCD (at most 3840 KiB).
- * Both ways write the same bytes.
+ * is used when only the expert tensor is written, k >= 2, the layout has at least 16 tiles, and the source
+ * rows of one tile (tile_tokens * (row_bytes + aux_row_bytes)) fit the 4 MB L2 of an XCD whole (at most
+ * 3840 KiB) or cut into two column segments of at least 4 KiB each, which are then moved in two passes over
+ * the tile.  Both ways write the same bytes.
  */
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags);
 

@@ -202,7 +202,7 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
     m.send_buf = nullptr; m.send_aux = nullptr;
     m.pair_slot = L->pair_slot; m.pair_send_row = L->pair_send_row; m.pair_first = L->pair_first;
-    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0;
+    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0; m.segs = 1; m.seg_chunks = 0;
     m.k = L->k;
     m.C = (int32_t)(row_bytes / 16); m.Ca = (int32_t)(aux_row_bytes / 16);
     m.write_expert = 1; m.write_wire = 0;
@@ -225,14 +225,33 @@ static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
 // fusco_probe_dispatch_kernel: 0 automatic; 1 keeps fusco_dispatch on the token walk (for comparisons)
 static std::atomic<int> g_dispatch_kernel{0};
 
+// Workgroup shape of the tiled dispatch for rows of Ct 16-byte chunks (both planes): the rows are cut into
+// `segs` column segments of `per` chunks, a tile being worked through once per segment, so that the segment
+// of the tile's source rows that is in use fits the L2 (kTiledMaxTileBytes).  A workgroup of `threads`
+// threads moves one segment of one row, cpt chunks per thread.  False when no shape fits: segments would be
+// narrower than 4 KiB.
+static bool tiled_shape(const fusco_layout *L, int Ct, int &threads, int &cpt, int &segs, int &per)
+{
+    const int max_chunks = (int)std::min<size_t>(1024, kTiledMaxTileBytes / 16 / (size_t)L->tile_tokens);
+    if (max_chunks < 1 || Ct < 1) return false;
+    segs = (Ct + max_chunks - 1) / max_chunks;
+    per = (Ct + segs - 1) / segs;
+    // measured at 8192 tokens x 8: two segments win up to 16 KiB rows (190 against 205 us at 15.5 KiB) and match
+    // the token walk up to 24 KiB; three and more lose to it (606 against 453 us at 32 KiB)
+    if (segs > 2 || (segs > 1 && per < 256)) return false;
+    cpt = per >= 512 ? 4 : (per >= 128 ? 2 : 1);
+    threads = std::min(256, round_up((per + cpt - 1) / cpt, kWave));
+    return true;
+}
+
 // the conditions under which fusco_dispatch moves the rows tile by tile in transfer order
 static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
                                        bool wire, bool two_hop)
 {
-    const size_t tile_source_bytes = (size_t)L->tile_tokens * (row_bytes + aux_row_bytes);
     if (g_dispatch_kernel.load(std::memory_order_relaxed) == 1) return false;
+    int threads, cpt, segs, per;
     return expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
-           tile_source_bytes <= kTiledMaxTileBytes;
+           tiled_shape(L, (int)((row_bytes + aux_row_bytes) / 16), threads, cpt, segs, per);
 }
 
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags)
@@ -274,17 +293,18 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.expert_buf = (u32x4 *)d_expert_buf; a.expert_aux = (u32x4 *)d_expert_aux;
     a.send_buf = (u32x4 *)d_send_buf; a.send_aux = (u32x4 *)d_send_aux;
     a.pair_slot = L->pair_slot; a.pair_send_row = L->pair_send_row; a.pair_first = L->pair_first;
-    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0;
+    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0; a.segs = 1; a.seg_chunks = 0;
     a.k = L->k;
     a.C = (int32_t)(row_bytes / 16);
     a.Ca = (int32_t)(aux_row_bytes / 16);
     a.write_expert = expert && !two_hop; a.write_wire = wire;
     const int Ct = a.C + a.Ca;
 
-    int cpt = Ct >= 512 ? 4 : (Ct >= 128 ? 2 : 1);
-    int threads = round_up((Ct + cpt - 1) / cpt, kWave);
-    if (threads > 256) threads = 256;
-    const int segs = (Ct + threads * cpt - 1) / (threads * cpt);
+    // token walk: as many column segments as workgroups of 256 threads x 4 chunks need, the chunks spread evenly
+    int segs = (Ct + 1023) / 1024;
+    int per = (Ct + segs - 1) / segs;
+    int cpt = per >= 512 ? 4 : (per >= 128 ? 2 : 1);
+    int threads = std::min(256, round_up((per + cpt - 1) / cpt, kWave));
     hipStream_t s = (hipStream_t)stream;
     ArmedEvents ev;
     if (two_hop) ev.start = ev.stop = nullptr;   // several kernels: armed events are dropped
@@ -294,6 +314,8 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     if (dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, expert, wire, two_hop)) {
         a.slot_token = L->slot_token; a.tile_slots = L->tile_slots;
         a.tile_cap = L->tile_tokens * L->k;
+        tiled_shape(L, Ct, threads, cpt, segs, per);
+        a.segs = segs; a.seg_chunks = per;
         // a source tensor that cannot stay in the memory-side cache is taken in chunks of whole rounds of tiles
         // whose rows fit half of it, every chunk after a sequential read of its source rows (touch_kernel)
         const size_t source_bytes = (size_t)L->N * (row_bytes + aux_row_bytes);
@@ -318,10 +340,12 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                     launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
                            a.x_aux + t0 * (size_t)a.Ca, na);
             }
-            const unsigned tblocks = (unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * kXcds;
+            const uint64_t blocks64 = (uint64_t)((tiles_here + kXcds - 1) / kXcds) * (uint64_t)a.tile_cap * (uint64_t)segs * kXcds;
+            if (blocks64 > 0x7fffffffu) return FUSCO_ERR_INVALID_ARG;
+            const unsigned tblocks = (unsigned)blocks64;
             hipEvent_t e0 = first && !chunked ? ev.start : nullptr, e1 = last ? ev.stop : nullptr;
             const uint32_t tb = (uint32_t)tile0, th = (uint32_t)tiles_here;
-            const dim3 tgrid(tblocks, (unsigned)segs);
+            const dim3 tgrid(tblocks);
 #define FUSCO_TILED(CPT)                                                                              \
     do {                                                                                              \
         if (a.Ca) launch_args(dispatch_tiled_kernel<CPT, true>, tgrid, tblock, s, e0, e1, a, tb, th); \
@@ -336,7 +360,9 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
         }
         return launch_status();
     }
-    const dim3 grid((unsigned)L->N, (unsigned)segs), block((unsigned)threads);
+    if ((uint64_t)L->N * (uint64_t)segs > 0x7fffffffu) return FUSCO_ERR_INVALID_ARG;
+    a.segs = segs; a.seg_chunks = per;
+    const dim3 grid((unsigned)L->N * (unsigned)segs), block((unsigned)threads);
     if (streaming) {
         switch (cpt) {
         case 1: launch(dispatch_kernel<1, true>, grid, block, s, a, ev.start, ev.stop); break;
@@ -406,9 +432,10 @@ int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, c
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
     a.pair_send_row = L->pair_send_row; a.send_src = L->send_src; a.n_rows_dev = L->send_off + L->D;
     a.first = 0;
-    int threads = round_up(a.C, kWave);
-    if (threads > 1024) threads = 1024;
-    const dim3 grid((unsigned)L->send_cap, (unsigned)((a.C + threads - 1) / threads));
+    a.n_rows = L->send_cap;
+    int threads;
+    combine_shape(a.C, threads, a.segs);
+    const dim3 grid((unsigned)L->send_cap * (unsigned)a.segs);
     if (y_dtype == FUSCO_BF16) hipLaunchKernelGGL((combine_kernel<true, false, 1, 8, true>), grid, dim3(threads), 0, s, a);
     else hipLaunchKernelGGL((combine_kernel<false, false, 1, 8, true>), grid, dim3(threads), 0, s, a);
     // level 1 reversed: sum of the token's partial rows

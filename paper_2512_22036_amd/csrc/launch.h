@@ -62,10 +62,22 @@ void launch_args(K kernel, dim3 grid, dim3 block, hipStream_t s, hipEvent_t e0, 
     else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
 }
 
-template <bool Y_BF16, bool OUT_BF16>
-void launch_combine(const CombineArgs &a, int N, int threads, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+// Workgroup shape of combine_kernel for rows of C chunks: as many column segments as 1024 threads need, the
+// threads spread evenly over them (1280 chunks: two workgroups of 640 threads, not 1024 + 256).
+inline void combine_shape(int C, int &threads, int &segs)
 {
-    const dim3 grid((unsigned)N, (unsigned)((a.C + threads - 1) / threads)), block((unsigned)threads);
+    segs = (C + 1023) / 1024;
+    if (segs < 1) segs = 1;
+    threads = round_up((C + segs - 1) / segs, kWave);
+}
+
+template <bool Y_BF16, bool OUT_BF16>
+void launch_combine(CombineArgs a, int N, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
+{
+    int threads;
+    combine_shape(a.C, threads, a.segs);
+    a.n_rows = N;
+    const dim3 grid((unsigned)N * (unsigned)a.segs), block((unsigned)threads);
     launch(combine_kernel<Y_BF16, OUT_BF16, 1, 8>, grid, block, s, a, e0, e1);
 }
 
@@ -141,13 +153,10 @@ void combine_launch(const int32_t *pair_slot, int N, int k, const void *d_y, int
     a.pair_send_row = nullptr; a.send_src = nullptr; a.n_rows_dev = nullptr;
     a.C = (int32_t)((size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4) / 16);
     a.first = combine_first_row(N, k, (size_t)a.C * 16);
-    // one workgroup per token whenever the row fits 1024 threads
-    int threads = round_up(a.C, kWave);
-    if (threads > 1024) threads = 1024;
-    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, threads, s, e0, e1);
-    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, threads, s, e0, e1);
-    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, threads, s, e0, e1);
-    else launch_combine<false, false>(a, N, threads, s, e0, e1);
+    if (y_dtype == FUSCO_BF16 && out_dtype == FUSCO_BF16) launch_combine<true, true>(a, N, s, e0, e1);
+    else if (y_dtype == FUSCO_BF16) launch_combine<true, false>(a, N, s, e0, e1);
+    else if (out_dtype == FUSCO_BF16) launch_combine<false, true>(a, N, s, e0, e1);
+    else launch_combine<false, false>(a, N, s, e0, e1);
 }
 
 }   // namespace

@@ -46,6 +46,8 @@ struct DispatchArgs {
     const uint8_t *pair_first;
     const int32_t *slot_token, *tile_slots;   // tiled mode: transfer order of every tile
     int32_t tile_cap;                         // entries per tile in tile_slots
+    int32_t segs;                             // workgroups per row: a row longer than a workgroup covers is cut into columns
+    int32_t seg_chunks;                       // 16-byte chunks per column segment (the last one may be shorter)
     int32_t k;
     int32_t C, Ca;   // 16-byte chunks per row in the main and in the aux plane
     int32_t write_expert, write_wire;
@@ -72,15 +74,18 @@ __device__ __forceinline__ void put16(u32x4 *p, u32x4 v)
 template <int CPT, bool STREAM = false>
 __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 {
-    const int t = blockIdx.x;
+    // workgroup = (token, column segment), segments of one row next to each other in launch order, so that a
+    // row longer than one workgroup covers is still read and written as a whole within a short time
+    const int t = blockIdx.x / (uint32_t)a.segs, seg = blockIdx.x - (uint32_t)t * a.segs;
     const int Ct = a.C + a.Ca;
-    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    const int c_end = min(Ct, (seg + 1) * a.seg_chunks);   // this segment: chunks [seg * seg_chunks, c_end)
+    const int c0 = seg * a.seg_chunks + threadIdx.x;
     u32x4 v[CPT];
 #pragma unroll
     for (int i = 0; i < CPT; ++i) {
         const int c = c0 + i * blockDim.x;
         const u32x4 *src = c < a.C ? a.x + (size_t)t * a.C + c : a.x_aux + (size_t)t * a.Ca + (c - a.C);
-        if (c < Ct) v[i] = STREAM ? *src : load16_stream(src);
+        if (c < c_end) v[i] = STREAM ? *src : load16_stream(src);
     }
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     if (a.write_expert) {
@@ -90,8 +95,9 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
+                if (c >= c_end) continue;
                 if (c < a.C) put16<STREAM>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
-                else if (c < Ct) put16<STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
+                else put16<STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -104,8 +110,9 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 #pragma unroll
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
+                if (c >= c_end) continue;
                 if (c < a.C) put16<STREAM>(a.send_buf + (size_t)row * a.C + c, v[i]);
-                else if (c < Ct) put16<STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
+                else put16<STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -115,45 +122,54 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 // hardware hands workgroups to the 8 XCDs in turn, so workgroup b = 8 i + x runs on XCD x; it takes entry
 // i mod cap of tile x + 8 (i / cap).  An XCD therefore works through whole tiles, one after the other, and
 // inside a tile it writes expert by expert: the rows of one expert are neighbours in memory, written by one
-// XCD within a short time, which is what the memory system rewards (measured on MI355X: the same bytes
-// written in runs of 100 KiB and more per XCD reach 6 TB/s and above, isolated 14 KiB rows 5.3 TB/s).  Every
-// source row is needed k times by the tile; it comes from memory once and from the XCD's L2 afterwards as
-// long as it is still there (plain cached loads; a tile's source rows fit the L2, but share it with the
-// destination rows passing through: at 3.5 MiB of source rows per tile the fabric counters show each row
-// fetched 1.4 times instead of once).  The rows are written with non-temporal stores: they are not kept in
-// the L2, which leaves it to the source rows, and they go past the memory-side cache, which the next reader
-// of memory would otherwise have to clean first and which so keeps a source tensor that fits it from one
-// call to the next.
+// XCD within a short time.  Every source row is needed k times by the tile; it comes from memory once and
+// from the XCD's L2 afterwards as long as it is still there (plain cached loads; a tile's source rows, or
+// the column segment of them that a pass moves, fit the L2 but share it with the destination rows passing
+// through: at 3.5 MiB of source rows per tile the fabric counters show each row fetched 1.4 times instead of
+// once).  The rows are written with non-temporal stores: they are not kept in the L2, which leaves it to the
+// source rows, and they go past the memory-side cache, which the next reader of memory would otherwise have
+// to clean first and which so keeps a source tensor that fits it from one call to the next.  Measured on
+// MI355X at 8192 tokens x 8 rows of 14 KiB: 175 us, which is what the same stores take without any loads
+// (180 us): the reads are hidden completely.  The token walk takes 205 us with non-temporal loads and plain
+// stores and 187 us with cached loads and non-temporal stores.
 // AUX: the second plane exists.  A chunk's source and destination are picked by address selection, not by
 // branching, so that the loads of a thread are issued back to back (a branch per chunk costs 3 % here).
 // The launch covers the tiles [tile_base, tile_base + tiles_here).
 template <int CPT, bool AUX>
 __global__ __launch_bounds__(256) void dispatch_tiled_kernel(DispatchArgs a, uint32_t tile_base, uint32_t tiles_here)
 {
+    // a tile is worked through a.segs times, once per column segment of the rows (one pass for rows that a
+    // workgroup covers): the L2 then only has to hold that segment of the tile's source rows
     const uint32_t b = blockIdx.x, x = b & (kXcds - 1), i = b / kXcds;
-    const uint32_t round = i / (uint32_t)a.tile_cap, r = i - round * (uint32_t)a.tile_cap;
+    const uint32_t per_tile = (uint32_t)a.tile_cap * (uint32_t)a.segs;
+    const uint32_t round = i / per_tile, w = i - round * per_tile;
+    const uint32_t pass = w / (uint32_t)a.tile_cap, r = w - pass * (uint32_t)a.tile_cap;
     const uint32_t local = x + kXcds * round;
     if (local >= tiles_here) return;
     const uint32_t tile = tile_base + local;
     const int slot = a.tile_slots[(size_t)tile * a.tile_cap + r];
     if (slot < 0) return;
     const int t = a.slot_token[slot];
+    // which segment a pass moves rotates with the token: the segments in use during a pass then lie at different
+    // offsets in their rows, and rows whose size is a power of two do not all fall on the same sets of the L2
+    const uint32_t seg = a.segs > 1 ? (pass + (uint32_t)t) % (uint32_t)a.segs : 0u;
     const int Ct = AUX ? a.C + a.Ca : a.C;
-    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    const int c_end = min(Ct, (int)(seg + 1) * a.seg_chunks);   // this segment: chunks [seg * seg_chunks, c_end)
+    const int c0 = seg * a.seg_chunks + threadIdx.x;
     u32x4 v[CPT];
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = c0 + q * blockDim.x;
         const u32x4 *src = a.x + (size_t)t * a.C + c;
         if (AUX && c >= a.C) src = a.x_aux + (size_t)t * a.Ca + (c - a.C);
-        if (c < Ct) v[q] = *src;
+        if (c < c_end) v[q] = *src;
     }
 #pragma unroll
     for (int q = 0; q < CPT; ++q) {
         const int c = c0 + q * blockDim.x;
         u32x4 *dst = a.expert_buf + (size_t)slot * a.C + c;
         if (AUX && c >= a.C) dst = a.expert_aux + (size_t)slot * a.Ca + (c - a.C);
-        if (c < Ct) __builtin_nontemporal_store(v[q], dst);
+        if (c < c_end) __builtin_nontemporal_store(v[q], dst);
     }
 }
 
@@ -231,6 +247,8 @@ struct CombineArgs {
     int32_t k;
     int32_t C;   // 16-byte chunks per y row
     int32_t first;   // row handled by workgroup 0; the walk goes upwards from there and wraps around
+    int32_t n_rows;  // rows of the walk (tokens, or send rows in the per-send-row mode)
+    int32_t segs;    // workgroups per row: the columns of a row longer than one workgroup covers
     // per-send-row mode (level 2 reversed): one workgroup per send row, only the token's entries on that row
     const int32_t *pair_send_row, *send_src, *n_rows_dev;
 };
@@ -253,14 +271,16 @@ __global__ __launch_bounds__(1024) void combine_kernel(CombineArgs a)
     // The walk starts at row a.first and wraps: when combine follows dispatch, the rows of the last
     // tokens are still in the memory-side cache, and reading them first, oldest first, finds them
     // there before the walk's own traffic pushes them out (see combine_first_row).
-    int r = a.first + (int)blockIdx.x;   // token, or send row in the per-send-row mode
-    if (r >= (int)gridDim.x) r -= (int)gridDim.x;
+    // workgroup = (row, column segment), the segments of one row next to each other in launch order
+    const int walk = blockIdx.x / (uint32_t)a.segs, seg = blockIdx.x - (uint32_t)walk * a.segs;
+    int r = a.first + walk;   // token, or send row in the per-send-row mode
+    if (r >= a.n_rows) r -= a.n_rows;
     int t = r;
     if constexpr (PER_SEND_ROW) {
         if (r >= *a.n_rows_dev) return;
         t = a.send_src[r];
     }
-    const int c0 = blockIdx.y * (blockDim.x * CPT) + threadIdx.x;
+    const int c0 = seg * (blockDim.x * CPT) + threadIdx.x;
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     const float *wt = a.w + (size_t)t * a.k;
 

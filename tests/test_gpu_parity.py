@@ -380,6 +380,7 @@ COMBINE_SHAPES = [
     (40, 1, 4, 2, 512), (33, 9, 18, 6, 8 * 129), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096),
     (3, 2, 4, 2, 1 << 19),         # the largest row (1 MiB of bf16)
     (4, 3, 6, 2, 8 * 8191 + 8),
+    (70, 8, 32, 4, 8 * 1285),      # 1285 chunks: two column segments of 643 and 642
 ]
 
 
@@ -599,8 +600,13 @@ TILED_SHAPES = [
     (4100, 8, 32, 8, 6144, 0, True),          # one and a half pieces per row, long runs (32 experts)
     (4200, 8, 256, 8, 5008, 48, True),        # an odd number of 16-byte units per row, short runs, a second plane
     (2100, 16, 64, 8, 18448, 0, True),        # 1153 units: two workgroup columns; 128 tokens per tile
-    (1100, 32, 64, 8, 41008, 16, True),       # 2563 units: three workgroup columns; 64 tokens per tile
+    (1100, 32, 64, 8, 28688, 16, True),       # 1794 chunks with the second plane: two segments; 64 tokens per tile
     (6000, 6, 10, 5, 4112, 0, False),         # repeated experts inside a token: neighbouring slots from one token
+    # rows that are moved in column segments (the source rows of a tile would not fit the L2 whole)
+    (4200, 8, 64, 8, 16384, 0, True),         # two segments of 8 KiB
+    (4200, 8, 64, 8, 20496, 64, True),        # two uneven planes over two segments: 1285 chunks
+    (8300, 4, 32, 8, 14336, 0, True),         # 512 tokens per tile: two segments of 7 KiB
+    (2100, 16, 64, 8, 30736, 0, True),        # 128 tokens per tile: two segments of 961 and 960 chunks
 ]
 
 
@@ -699,7 +705,12 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
     assert not fusco.fusco_dispatch_in_transfer_order(small, 2048)
     assert fusco.fusco_dispatch_in_transfer_order(many, 14336)
     assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 224)
-    assert fusco.fusco_dispatch_in_transfer_order(many, 15360) and not fusco.fusco_dispatch_in_transfer_order(many, 15376)
+    # rows longer than 15 KiB are moved in column segments, one pass over the tile per segment
+    assert fusco.fusco_dispatch_in_transfer_order(many, 15360) and fusco.fusco_dispatch_in_transfer_order(many, 15376)
+    assert fusco.fusco_dispatch_in_transfer_order(many, 30720) and not fusco.fusco_dispatch_in_transfer_order(many, 30736)
+    wide = fusco.Layout(40000, 2, 64, 8)             # 1024 tokens per tile: a segment may hold 3840 B of a row
+    assert fusco.fusco_dispatch_in_transfer_order(wide, 3840) and not fusco.fusco_dispatch_in_transfer_order(wide, 4096)
+    assert not fusco.fusco_dispatch_in_transfer_order(wide, 16384)   # segments would be narrower than 4 KiB
     assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_WIRE)
     assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
     assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_STREAMING)

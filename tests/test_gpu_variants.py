@@ -139,7 +139,8 @@ def test_disaggregated_baseline_matches_oracle(fusco, oracle, N, k, E, D, H):
 
 
 TWO_HOP_COMBINE_SHAPES = [(50, 2, 8, 4, 8), (300, 8, 256, 8, 7168), (65, 4, 16, 4, 296), (129, 8, 64, 64, 1024),
-                          (90, 3, 6, 1, 512), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096)]
+                          (90, 3, 6, 1, 512), (20, 17, 34, 2, 2056), (10, 64, 128, 8, 4096),
+                          (12, 9, 18, 3, 8 * 1285)]       # rows of two and three uneven column segments, general k
 
 
 @pytest.mark.parametrize("N,k,E,D,H", TWO_HOP_COMBINE_SHAPES)
