@@ -345,6 +345,45 @@ def row_sweep(fusco, torch, np, W, reps=30):
     return {"N": cfg.N, "k": cfg.k, "E": cfg.E, "reps": reps, "sizes": rows}
 
 
+def token_sweep(fusco, torch, np, W, reps=20):
+    """Plan, dispatch and combine over the token count, with the dsv3 workload's shape (bf16 rows of 14336 B, top-8 of
+    256 experts, the same seeded routing recipe), per-call kernel times as in the benchmark line."""
+    base = W.get_config("dsv3")
+    rows = []
+    for N in (1024, 2048, 4096, 8192, 12288, 16384, 32768, 65536):
+        cfg = base.with_tokens(N)
+        A, w = W.make_routing(cfg)
+        d_A, d_w = torch.from_numpy(A).cuda(), torch.from_numpy(w).cuda()
+        L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+        x = torch.randn((cfg.N, cfg.H), device="cuda").to(torch.bfloat16)
+        eb = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda")
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(reps)]
+        for r in ev:
+            for e in r:
+                e.record()
+        for _ in range(3):
+            fusco.fusco_plan(L, d_A)
+            fusco.fusco_dispatch(L, x, eb)
+            fusco.fusco_combine(L, eb, d_w, out)
+        torch.cuda.synchronize()
+        for i in range(reps):
+            fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
+            fusco.fusco_plan(L, d_A)
+            fusco.fusco_probe_time_next_call(ev[i][2], ev[i][3])
+            fusco.fusco_dispatch(L, x, eb)
+            fusco.fusco_probe_time_next_call(ev[i][4], ev[i][5])
+            fusco.fusco_combine(L, eb, d_w, out)
+        torch.cuda.synchronize()
+        p, d, c = (float(np.mean([ev[i][2 * j].elapsed_time(ev[i][2 * j + 1]) for i in range(reps)])) * 1e3 for j in range(3))
+        nb = (cfg.N + cfg.P) * cfg.row_bytes
+        rows.append({"N": N, "tiles": L.tile_count, "transfer_order": bool(fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes)),
+                     "source_MB": cfg.N * cfg.row_bytes / 1e6, "plan_us": p, "dispatch_us": d, "dispatch_GBps": nb / d / 1e3,
+                     "combine_us": c, "combine_GBps": nb / c / 1e3, "frac_of_peak": 2 * nb / ((d + c) * 1e-6) / 1e9 / HBM_PEAK_GBS})
+        del x, eb, out, L
+    return {"row_bytes": base.row_bytes, "k": base.k, "E": base.E, "reps": reps, "sizes": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -372,6 +411,8 @@ def main() -> int:
                     help="instead of the benchmark line, print fusco_plan's time for 8 Ki to 2 Mi tokens")
     ap.add_argument("--row-sweep", action="store_true",
                     help="instead of the benchmark line, print dispatch and combine times for hidden sizes 2048 ... 24576")
+    ap.add_argument("--token-sweep", action="store_true",
+                    help="instead of the benchmark line, print plan, dispatch and combine times for 1 Ki to 64 Ki tokens")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -394,6 +435,9 @@ def main() -> int:
     cfg = W.get_config(args.config)
     if args.cache_probe:
         print(json.dumps({"cache_probe": cache_probe(fusco, torch, cfg.row_bytes)}))
+        return 0
+    if args.token_sweep:
+        print(json.dumps({"token_sweep": token_sweep(fusco, torch, np, W)}))
         return 0
     if args.row_sweep:
         print(json.dumps({"row_sweep": row_sweep(fusco, torch, np, W)}))
