@@ -391,7 +391,7 @@ int fusco_combine(const fusco_layout *L, const void *d_y, int y_dtype, const flo
 {
     if (!layout_ok(L)) return FUSCO_ERR_INVALID_ARG;
     if (flags != 0) return FUSCO_ERR_UNSUPPORTED;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0, (int64_t)L->N);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     const ArmedEvents ev;
     combine_launch(L->pair_slot, L->N, L->k, d_y, y_dtype, d_w, d_out, out_dtype, H, (hipStream_t)stream, ev.start,
@@ -403,7 +403,7 @@ int fusco_combine_two_hop(const fusco_layout *L, const void *d_y, int y_dtype, c
                           void *d_out, int out_dtype, int32_t H, void *stream)
 {
     if (!layout_ok(L) || (!d_partial && L->N > 0) || !aligned16(d_partial)) return FUSCO_ERR_INVALID_ARG;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0, (int64_t)L->send_cap);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (L->k <= 8) {
@@ -496,7 +496,7 @@ int fusco_disaggregated_combine(const fusco_layout *L, const fusco_layout *Lr, c
                                 int32_t H, void *stream)
 {
     if (!rank_layout_matches(L, Lr)) return FUSCO_ERR_INVALID_ARG;
-    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0);
+    const int rc = combine_check(d_y, y_dtype, d_w, d_out, out_dtype, H, L->N == 0, (int64_t)L->N);
     if (rc != FUSCO_OK || L->N == 0) return rc;
     if (!d_stage_a || !d_stage_b || !aligned16(d_stage_a) || !aligned16(d_stage_b)) return FUSCO_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;

@@ -111,8 +111,9 @@ void launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s)
 }
 
 // `empty`: the layout has no tokens, so the tensors hold no rows and may be NULL
+// walk_rows: rows the combine walks over (tokens, or send rows); the launch needs a workgroup per row and column segment
 int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_out, int out_dtype, int32_t H,
-                  bool empty)
+                  bool empty, int64_t walk_rows)
 {
     if (H <= 0 || (!empty && (!d_y || !d_w || !d_out))) return FUSCO_ERR_INVALID_ARG;
     if ((y_dtype != FUSCO_BF16 && y_dtype != FUSCO_F32) || (out_dtype != FUSCO_BF16 && out_dtype != FUSCO_F32))
@@ -120,6 +121,9 @@ int combine_check(const void *d_y, int y_dtype, const float *d_w, const void *d_
     const size_t y_row = (size_t)H * (y_dtype == FUSCO_BF16 ? 2 : 4);
     if (y_row % 16 != 0 || y_row / 16 > kMaxRowChunks) return FUSCO_ERR_INVALID_ARG;
     if (!aligned16(d_y) || !aligned16(d_out) || ((uintptr_t)d_w & 3u)) return FUSCO_ERR_INVALID_ARG;
+    int threads, segs;
+    combine_shape((int)(y_row / 16), threads, segs);
+    if (walk_rows * segs > 0x7fffffff) return FUSCO_ERR_INVALID_ARG;
     return FUSCO_OK;
 }
 
