@@ -185,7 +185,9 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
  * is used when only the expert tensor is written, k >= 2, the layout has at least 16 tiles, and the source
  * rows of one tile (tile_tokens * (row_bytes + aux_row_bytes)) fit the 4 MB L2 of an XCD whole (at most
  * 3840 KiB) or cut into two column segments of at least 4 KiB each, which are then moved in two passes over
- * the tile.  Both ways write the same bytes.
+ * the tile; and when the sizes make it pay: the expert tensor is larger than the 256 MB memory-side cache
+ * (a smaller one is left there by the token walk's plain stores for its reader), and rows shorter than 8 KiB
+ * come with a source tensor of less than 128 MiB.  Both ways write the same bytes.
  */
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags);
 

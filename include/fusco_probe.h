@@ -69,10 +69,11 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
                                const uint32_t *d_slice_fill, uint32_t max_polls, uint32_t *d_report, void *stream);
 
 /*
- * Study aid: which kernel every later fusco_dispatch of the process uses where it has a choice.  0: automatic.
- * 1: the token walk (one workgroup per token), also where the rows would be moved tile by tile in transfer
- * order; fusco_dispatch_in_transfer_order reflects it.  which < 0 only reads the setting.  Returns the previous
- * setting, FUSCO_ERR_INVALID_ARG for which > 1.  The result of fusco_dispatch does not depend on it.
+ * Study and test aid: which kernel every later fusco_dispatch of the process uses where it has a choice.
+ * 0: automatic.  1: the token walk (one workgroup per token), also where the rows would be moved tile by tile in
+ * transfer order.  2: the transfer order wherever its workgroup shape allows, also at sizes where the token walk
+ * is preferred.  fusco_dispatch_in_transfer_order reflects the setting.  which < 0 only reads it.  Returns the
+ * previous setting, FUSCO_ERR_INVALID_ARG for which > 2.  The result of fusco_dispatch does not depend on it.
  */
 int fusco_probe_dispatch_kernel(int which);
 

@@ -387,8 +387,8 @@ def fusco_probe_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
 
 
 def fusco_probe_dispatch_kernel(which: int = -1) -> int:
-    """Which kernel fusco_dispatch uses where it has a choice: 0 automatic, 1 token walk; < 0 reads the setting.
-    Returns the previous setting."""
+    """Which kernel fusco_dispatch uses where it has a choice: 0 automatic, 1 token walk, 2 transfer order wherever
+    its shape allows; < 0 reads the setting.  Returns the previous setting."""
     rc = int(load_library().fusco_probe_dispatch_kernel(int(which)))
     if rc < 0:
         _check(rc, "fusco_probe_dispatch_kernel")

@@ -222,7 +222,8 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
 // largest source tensor that the tiled dispatch takes in one piece (fusco_probe_source_chunk_bytes changes it)
 static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
 
-// fusco_probe_dispatch_kernel: 0 automatic; 1 keeps fusco_dispatch on the token walk (for comparisons)
+// fusco_probe_dispatch_kernel: 0 automatic; 1 keeps fusco_dispatch on the token walk; 2 takes the transfer order
+// wherever its shape allows, whatever the sizes (for comparisons and tests)
 static std::atomic<int> g_dispatch_kernel{0};
 
 // Workgroup shape of the tiled dispatch for rows of Ct 16-byte chunks (both planes): the rows are cut into
@@ -248,10 +249,21 @@ static bool tiled_shape(const fusco_layout *L, int Ct, int &threads, int &cpt, i
 static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, bool expert,
                                        bool wire, bool two_hop)
 {
-    if (g_dispatch_kernel.load(std::memory_order_relaxed) == 1) return false;
+    const int which = g_dispatch_kernel.load(std::memory_order_relaxed);
+    if (which == 1) return false;
     int threads, cpt, segs, per;
-    return expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
-           tiled_shape(L, (int)((row_bytes + aux_row_bytes) / 16), threads, cpt, segs, per);
+    if (!(expert && !wire && !two_hop && L->k >= 2 && L->tile_count >= kTiledMinTiles &&
+          tiled_shape(L, (int)((row_bytes + aux_row_bytes) / 16), threads, cpt, segs, per)))
+        return false;
+    if (which == 2) return true;
+    // Sizes at which the token walk is as good or better (measured, 8 rows per token):
+    // - an expert tensor that fits the memory-side cache: the walk's plain stores leave it there for its reader;
+    // - rows shorter than 8 KiB together with a source tensor that does not stay in that cache next to the
+    //   output of a combine of the same size (from 128 MiB on): the tiles' short runs then lose to the walk.
+    const size_t row = row_bytes + aux_row_bytes;
+    if ((size_t)L->P * row <= kCacheBytes) return false;
+    if (row < kTiledShortRowBytes && (size_t)L->N * row >= g_source_chunk_bytes.load(std::memory_order_relaxed)) return false;
+    return true;
 }
 
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags)
@@ -662,7 +674,7 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
 
 int fusco_probe_dispatch_kernel(int which)
 {
-    if (which > 1) return FUSCO_ERR_INVALID_ARG;
+    if (which > 2) return FUSCO_ERR_INVALID_ARG;
     return which < 0 ? g_dispatch_kernel.load() : g_dispatch_kernel.exchange(which);
 }
 

@@ -57,6 +57,8 @@ constexpr int kXcds = 8;                                  // accelerator complex
 constexpr int kTiledMinTiles = 2 * kXcds;                 // fewer tiles would leave XCDs idle
 constexpr size_t kTiledMaxTileBytes = (size_t)3840 << 10; // source rows of one tile must fit a 4 MB L2
 constexpr size_t kSourceChunkBytes = (size_t)128 << 20;   // source rows of one chunk: half the 256 MB memory-side cache
+constexpr size_t kCacheBytes = (size_t)256 << 20;         // the memory-side cache
+constexpr size_t kTiledShortRowBytes = 8192;              // rows below this are tiled only with a small source tensor
 
 // STREAM: the rows are written with non-temporal stores, which go past the memory-side cache (measured: a
 // read that follows such a write runs at the cold rate, 5.7 TB/s for 256 MB, instead of 4.2 TB/s on rows

@@ -239,7 +239,8 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_source_chunk_bytes(128 << 20) == 1 << 20
     assert lib.fusco_probe_dispatch_kernel(-1) == 0 and lib.fusco_probe_dispatch_kernel(1) == 0
     assert lib.fusco_probe_dispatch_kernel(-1) == 1 and lib.fusco_probe_dispatch_kernel(0) == 1
-    assert lib.fusco_probe_dispatch_kernel(2) == -1 and lib.fusco_probe_dispatch_kernel(-1) == 0
+    assert lib.fusco_probe_dispatch_kernel(2) == 0 and lib.fusco_probe_dispatch_kernel(0) == 2
+    assert lib.fusco_probe_dispatch_kernel(3) == -1 and lib.fusco_probe_dispatch_kernel(-1) == 0
     pp = lib.fusco_probe_pieces
     assert pp(None, 1 << 20, 1, 1, 0, None, None) == -1
     assert pp(buf, (1 << 20) + 16, 1, 1, 0, None, None) == -1              # not whole pieces

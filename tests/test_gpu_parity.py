@@ -118,6 +118,7 @@ def test_random_shapes_whole_path(fusco, oracle):
     plan, dispatch (expert and wire tensors, both planes) and combine against the oracle, element by element."""
     rng = np.random.default_rng(20251127)
     seen_chunks = set()
+    seen_tiled = 0
     for case in range(300):
         N, k, E, D, distinct = _random_shape(rng)
         # 16-byte units per row: up to 64 for any shape, up to 1152 (18 KiB) where the expert tensor stays small
@@ -158,6 +159,17 @@ def test_random_shapes_whole_path(fusco, oracle):
             assert np.array_equal(sa[:want.U].cpu().numpy().view(np.uint32), send_aux_want), tag
         _, o16 = oracle.combine_f32(expert_want, w, want.pair_slot)
         assert np.array_equal(bits_host(out), o16), tag
+        # the expert tensor alone, in transfer order wherever the shape allows it (16 tiles and more)
+        eb3 = torch.zeros_like(eb)
+        ea3 = torch.zeros_like(ea) if Ca else None
+        fusco.fusco_probe_dispatch_kernel(2)
+        try:
+            seen_tiled += bool(fusco.fusco_dispatch_in_transfer_order(L, H * 2, Ca * 16))
+            fusco.fusco_dispatch(L, bf16_dev(xb), eb3, x_aux=dev(xa.view(np.int32)) if Ca else None, expert_aux=ea3)
+            torch.cuda.synchronize()
+        finally:
+            fusco.fusco_probe_dispatch_kernel(0)
+        assert torch.equal(eb3, eb) and (not Ca or torch.equal(ea3, ea)), tag
         if N <= 2048 // k:                                      # the single-launch path gives the same
             L2 = fusco.Layout(N, k, E, D)
             eb2 = torch.zeros_like(eb)
@@ -175,6 +187,7 @@ def test_random_shapes_whole_path(fusco, oracle):
             if Ca:
                 assert torch.equal(ea2, ea), tag
     assert seen_chunks == {1, 2, 4}          # one, two and four 16-byte chunks per thread were all exercised
+    assert seen_tiled >= 15                  # and the tiled dispatch took its share of the shapes (21 of these 300)
 
 
 def test_plan_empty_input(fusco, oracle):
@@ -586,6 +599,15 @@ def test_binding_rejects_wrong_shapes(fusco):
         fusco.Layout(16, 2, 4, 3)
 
 
+@pytest.fixture
+def transfer_order_everywhere(fusco):
+    """The tests of the tiled dispatch run it on small inputs, where fusco_dispatch would walk the tokens: the study
+    knob takes the transfer order wherever its workgroup shape allows."""
+    assert fusco.fusco_probe_dispatch_kernel(2) == 0
+    yield
+    assert fusco.fusco_probe_dispatch_kernel(0) == 2
+
+
 TILED_SHAPES = [
     # N, k, E, D, row_bytes, aux_row_bytes, distinct: inputs of at least 16 tiles of 2048 pairs whose tile of source
     # rows fits an XCD's L2, so that dispatch moves the rows in transfer order
@@ -611,7 +633,8 @@ TILED_SHAPES = [
 
 
 @pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", TILED_SHAPES)
-def test_dispatch_in_transfer_order_matches_oracle(fusco, oracle, N, k, E, D, row_bytes, aux_bytes, distinct):
+def test_dispatch_in_transfer_order_matches_oracle(fusco, oracle, transfer_order_everywhere, N, k, E, D, row_bytes, aux_bytes,
+                                                   distinct):
     rng = np.random.default_rng(N + row_bytes)
     A = random_topk(rng, N, k, E, distinct)
     x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
@@ -645,7 +668,8 @@ def test_dispatch_in_transfer_order_matches_oracle(fusco, oracle, N, k, E, D, ro
 
 @pytest.mark.parametrize("chunk_tiles", [8, 16])
 @pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", TILED_SHAPES)
-def test_dispatch_in_source_chunks_matches_oracle(fusco, oracle, chunk_tiles, N, k, E, D, row_bytes, aux_bytes, distinct):
+def test_dispatch_in_source_chunks_matches_oracle(fusco, oracle, transfer_order_everywhere, chunk_tiles, N, k, E, D, row_bytes,
+                                                  aux_bytes, distinct):
     """Source tensors larger than the memory-side cache are moved in chunks of tiles, every chunk starting with a read
     of its source rows.  The chunk size is lowered here so that small inputs take that path: 8 tiles (the smallest,
     a last chunk with fewer tiles than XCDs for the 17- and 35-tile inputs) and 16 tiles."""
@@ -676,7 +700,7 @@ def test_dispatch_in_source_chunks_matches_oracle(fusco, oracle, chunk_tiles, N,
     assert np.array_equal(eb.cpu().numpy(), expert_want)
 
 
-def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle):
+def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle, transfer_order_everywhere):
     rng = np.random.default_rng(5)
     N, k, E, D, row_bytes = 5000, 8, 64, 8, 1024
     A = random_topk(rng, N, k, E).reshape(-1)
@@ -699,22 +723,30 @@ def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle):
 
 
 def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(fusco):
+    tiled = fusco.fusco_dispatch_in_transfer_order
     small = fusco.Layout(1000, 8, 64, 8)             # 4 tiles: too few for the eight XCDs
     many = fusco.Layout(8192, 8, 256, 8)             # 32 tiles of 256 tokens
     top1 = fusco.Layout(65536, 1, 64, 8)             # k = 1: a row is used once, nothing to keep in the L2
-    assert not fusco.fusco_dispatch_in_transfer_order(small, 2048)
-    assert fusco.fusco_dispatch_in_transfer_order(many, 14336)
-    assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 224)
-    # rows longer than 15 KiB are moved in column segments, one pass over the tile per segment
-    assert fusco.fusco_dispatch_in_transfer_order(many, 15360) and fusco.fusco_dispatch_in_transfer_order(many, 15376)
-    assert fusco.fusco_dispatch_in_transfer_order(many, 30720) and not fusco.fusco_dispatch_in_transfer_order(many, 30736)
     wide = fusco.Layout(40000, 2, 64, 8)             # 1024 tokens per tile: a segment may hold 3840 B of a row
-    assert fusco.fusco_dispatch_in_transfer_order(wide, 3840) and not fusco.fusco_dispatch_in_transfer_order(wide, 4096)
-    assert not fusco.fusco_dispatch_in_transfer_order(wide, 16384)   # segments would be narrower than 4 KiB
-    assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_WIRE)
-    assert not fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
-    assert fusco.fusco_dispatch_in_transfer_order(many, 14336, 0, fusco.DISPATCH_STREAMING)
-    assert not fusco.fusco_dispatch_in_transfer_order(top1, 2048)
+    long = fusco.Layout(65536, 8, 256, 8)
+    # sizes: an expert tensor that fits the memory-side cache is left to the token walk, and so are rows shorter
+    # than 8 KiB when the source tensor has 128 MiB or more
+    assert tiled(many, 14336) and tiled(many, 14336, 224) and tiled(many, 4112)
+    assert not tiled(many, 4096) and not tiled(many, 2048)              # 256 MiB and 128 MiB of expert rows
+    assert tiled(long, 2032) and not tiled(long, 2048) and not tiled(long, 4096) and tiled(long, 8192)
+    assert fusco.fusco_probe_dispatch_kernel(2) == 0
+    try:
+        # workgroup shapes: the whole tile's source rows, or two column segments of them, must fit an XCD's L2
+        assert not tiled(small, 2048) and not tiled(top1, 2048)
+        assert tiled(many, 2048) and tiled(long, 4096)
+        assert tiled(many, 15360) and tiled(many, 15376)                # one segment, two segments
+        assert tiled(many, 30720) and not tiled(many, 30736)            # three segments: token walk
+        assert tiled(wide, 3840) and not tiled(wide, 4096)              # segments would be narrower than 4 KiB
+        assert not tiled(wide, 16384)
+        assert not tiled(many, 14336, 0, fusco.DISPATCH_WIRE) and not tiled(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
+        assert tiled(many, 14336, 0, fusco.DISPATCH_STREAMING)
+    finally:
+        assert fusco.fusco_probe_dispatch_kernel(0) == 2
 
 
 def test_dispatch_kept_on_the_token_walk_gives_the_same_rows(fusco, oracle):
@@ -725,15 +757,15 @@ def test_dispatch_kept_on_the_token_walk_gives_the_same_rows(fusco, oracle):
     x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
     want = oracle.plan(A, E, D)
     L, got = gpu_plan(fusco, A, E, D)
-    assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
     eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
-    assert fusco.fusco_probe_dispatch_kernel(1) == 0
+    assert fusco.fusco_probe_dispatch_kernel(2) == 0 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+    assert fusco.fusco_probe_dispatch_kernel(1) == 2
     try:
         assert not fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
         fusco.fusco_dispatch(L, dev(x), eb)
         torch.cuda.synchronize()
     finally:
         fusco.fusco_probe_dispatch_kernel(0)
-    assert fusco.fusco_probe_dispatch_kernel() == 0 and fusco.fusco_dispatch_in_transfer_order(L, row_bytes)
+    assert fusco.fusco_probe_dispatch_kernel() == 0
     _, expert_want = oracle.dispatch(want, x)
     assert np.array_equal(eb.cpu().numpy(), expert_want)
