@@ -187,7 +187,8 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
  * 3840 KiB) or cut into two column segments of at least 4 KiB each, which are then moved in two passes over
  * the tile; and when the sizes make it pay: the expert tensor is larger than the 256 MB memory-side cache
  * (a smaller one is left there by the token walk's plain stores for its reader), and rows shorter than 8 KiB
- * come with a source tensor of less than 128 MiB.  Both ways write the same bytes.
+ * come with a source tensor of at most 128 MiB (less than 128 MiB for rows shorter than 4 KiB).  Both ways
+ * write the same bytes.
  */
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags);
 

@@ -258,11 +258,14 @@ static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, 
     if (which == 2) return true;
     // Sizes at which the token walk is as good or better (measured, 8 rows per token):
     // - an expert tensor that fits the memory-side cache: the walk's plain stores leave it there for its reader;
-    // - rows shorter than 8 KiB together with a source tensor that does not stay in that cache next to the
-    //   output of a combine of the same size (from 128 MiB on): the tiles' short runs then lose to the walk.
-    const size_t row = row_bytes + aux_row_bytes;
+    // - rows shorter than 8 KiB together with a source tensor that would be taken in chunks (more than 128 MiB),
+    //   and rows shorter than 4 KiB already with one of 128 MiB, which does not stay in that cache next to the
+    //   output of a combine of the same size: the tiles' short runs then lose to the walk.
+    const size_t row = row_bytes + aux_row_bytes, source = (size_t)L->N * row;
+    const size_t limit = g_source_chunk_bytes.load(std::memory_order_relaxed);
     if ((size_t)L->P * row <= kCacheBytes) return false;
-    if (row < kTiledShortRowBytes && (size_t)L->N * row >= g_source_chunk_bytes.load(std::memory_order_relaxed)) return false;
+    if (row < kTiledShortRowBytes && source > limit) return false;
+    if (row < kTiledShortRowBytes / 2 && source >= limit) return false;
     return true;
 }
 

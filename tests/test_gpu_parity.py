@@ -734,6 +734,8 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
     assert tiled(many, 14336) and tiled(many, 14336, 224) and tiled(many, 4112)
     assert not tiled(many, 4096) and not tiled(many, 2048)              # 256 MiB and 128 MiB of expert rows
     assert tiled(long, 2032) and not tiled(long, 2048) and not tiled(long, 4096) and tiled(long, 8192)
+    half = fusco.Layout(32768, 8, 256, 8)
+    assert tiled(half, 4096) and not tiled(half, 4112) and tiled(half, 2048)       # 128 MiB of source rows, just more, half
     assert fusco.fusco_probe_dispatch_kernel(2) == 0
     try:
         # workgroup shapes: the whole tile's source rows, or two column segments of them, must fit an XCD's L2
