@@ -341,6 +341,9 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
             chunk_tiles = chunk_limit / ((size_t)L->tile_tokens * (row_bytes + aux_row_bytes)) / kXcds * kXcds;
             if (chunk_tiles < (size_t)kXcds) chunk_tiles = kXcds;
         }
+        // the largest launch: a workgroup per row and segment of the chunk's tiles (checked before anything is launched)
+        if ((uint64_t)((chunk_tiles + kXcds - 1) / kXcds) * (uint64_t)a.tile_cap * (uint64_t)segs * kXcds > 0x7fffffffu)
+            return FUSCO_ERR_INVALID_ARG;
         const dim3 tblock((unsigned)threads);
         for (size_t tile0 = 0; tile0 < (size_t)L->tile_count; tile0 += chunk_tiles) {
             const size_t tiles_here = std::min(chunk_tiles, (size_t)L->tile_count - tile0);
@@ -355,9 +358,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                     launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
                            a.x_aux + t0 * (size_t)a.Ca, na);
             }
-            const uint64_t blocks64 = (uint64_t)((tiles_here + kXcds - 1) / kXcds) * (uint64_t)a.tile_cap * (uint64_t)segs * kXcds;
-            if (blocks64 > 0x7fffffffu) return FUSCO_ERR_INVALID_ARG;
-            const unsigned tblocks = (unsigned)blocks64;
+            const unsigned tblocks = (unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * (unsigned)segs * kXcds;
             hipEvent_t e0 = first && !chunked ? ev.start : nullptr, e1 = last ? ev.stop : nullptr;
             const uint32_t tb = (uint32_t)tile0, th = (uint32_t)tiles_here;
             const dim3 tgrid(tblocks);
