@@ -27,8 +27,8 @@ def test_bench_reads_its_traffic_figures_from_the_summary():
     assert set(got) == {"dispatch", "combine"}
     # combine: every row once - no wasted re-reads, and nothing the counters could have missed
     assert algorithmic <= got["combine"] <= 1.01 * algorithmic, got
-    # dispatch: a tile's source rows share an XCD's L2 with the destination rows streaming through it and part of
-    # them is fetched again (from the memory-side cache); the summary states the share, bounded here
-    assert algorithmic <= got["dispatch"] <= 1.06 * algorithmic, got
+    # dispatch: a tile's source rows are fetched once and stay in the XCD's L2 (write-through non-temporal stores do
+    # not displace them; with plain non-temporal stores the figure was 1.047)
+    assert algorithmic <= got["dispatch"] <= 1.01 * algorithmic, got
     assert bench.measured_traffic("qwen3") == {}          # no summary for other workloads: reported as null
     assert "MEASURED_TRAFFIC_BYTES" not in open(os.path.join(ROOT, "bench.py")).read()
