@@ -315,7 +315,7 @@ def row_sweep(fusco, torch, np, W, reps=30):
     torch.cuda.synchronize()
     first = L.array("pair_slot").long()[::cfg.k][:64]
     rows = []
-    for H in (2048, 4096, 6144, 7168, 7680, 7936, 8192, 10240, 12288, 16384, 24576):
+    for H in (2048, 4096, 6144, 7168, 7680, 7936, 8192, 10240, 12288, 16384, 20480, 24576, 32768):
         x = torch.randn((cfg.N, H), device="cuda").to(torch.bfloat16)
         eb = torch.empty((cfg.P, H), dtype=torch.bfloat16, device="cuda")
         out = torch.empty((cfg.N, H), dtype=torch.bfloat16, device="cuda")
@@ -410,7 +410,7 @@ def main() -> int:
     ap.add_argument("--plan-scaling", action="store_true",
                     help="instead of the benchmark line, print fusco_plan's time for 8 Ki to 2 Mi tokens")
     ap.add_argument("--row-sweep", action="store_true",
-                    help="instead of the benchmark line, print dispatch and combine times for hidden sizes 2048 ... 24576")
+                    help="instead of the benchmark line, print dispatch and combine times for hidden sizes 2048 ... 32768")
     ap.add_argument("--token-sweep", action="store_true",
                     help="instead of the benchmark line, print plan, dispatch and combine times for 1 Ki to 64 Ki tokens")
     ap.add_argument("--probe-copy", action="store_true",

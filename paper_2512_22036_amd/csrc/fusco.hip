@@ -230,16 +230,19 @@ static std::atomic<int> g_dispatch_kernel{0};
 // `segs` column segments of `per` chunks, a tile being worked through once per segment, so that the segment
 // of the tile's source rows that is in use fits the L2 (kTiledMaxTileBytes).  A workgroup of `threads`
 // threads moves one segment of one row, cpt chunks per thread.  False when no shape fits: segments would be
-// narrower than 4 KiB.
+// narrower than 4 KiB, or more than 8.
 static bool tiled_shape(const fusco_layout *L, int Ct, int &threads, int &cpt, int &segs, int &per)
 {
-    const int max_chunks = (int)std::min<size_t>(1024, kTiledMaxTileBytes / 16 / (size_t)L->tile_tokens);
+    int max_chunks = (int)std::min<size_t>(1024, kTiledMaxTileBytes / 16 / (size_t)L->tile_tokens);
     if (max_chunks < 1 || Ct < 1) return false;
+    if (Ct > max_chunks) max_chunks = max_chunks / kWave * kWave;   // segments are whole KiB
+    if (max_chunks < 1) return false;
     segs = (Ct + max_chunks - 1) / max_chunks;
-    per = (Ct + segs - 1) / segs;
-    // measured at 8192 tokens x 8: two segments win up to 16 KiB rows (190 against 205 us at 15.5 KiB) and match
-    // the token walk up to 24 KiB; three and more lose to it (606 against 453 us at 32 KiB)
-    if (segs > 2 || (segs > 1 && per < 256)) return false;
+    per = segs > 1 ? round_up((Ct + segs - 1) / segs, kWave) : Ct;   // segments start on 1 KiB boundaries of the row
+    // measured at 8192 tokens x 8: two segments win up to 16 KiB rows (190 against 205 us at 15.5 KiB); from there
+    // to 64 KiB rows (five segments) the tiled kernel takes as long as the token walk, and the combine that follows
+    // is 5-8 % faster after it, because its stores leave nothing dirty in the memory-side cache
+    if (segs > 8 || (segs > 1 && per < 256)) return false;
     cpt = per >= 512 ? 4 : (per >= 128 ? 2 : 1);
     threads = std::min(256, round_up((per + cpt - 1) / cpt, kWave));
     return true;
@@ -317,7 +320,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
 
     // token walk: as many column segments as workgroups of 256 threads x 4 chunks need, the chunks spread evenly
     int segs = (Ct + 1023) / 1024;
-    int per = (Ct + segs - 1) / segs;
+    int per = segs > 1 ? round_up((Ct + segs - 1) / segs, kWave) : Ct;   // segments start on 1 KiB boundaries of the row
     int cpt = per >= 512 ? 4 : (per >= 128 ? 2 : 1);
     int threads = std::min(256, round_up((per + cpt - 1) / cpt, kWave));
     hipStream_t s = (hipStream_t)stream;

@@ -628,7 +628,9 @@ TILED_SHAPES = [
     (4200, 8, 64, 8, 16384, 0, True),         # two segments of 8 KiB
     (4200, 8, 64, 8, 20496, 64, True),        # two uneven planes over two segments: 1285 chunks
     (8300, 4, 32, 8, 14336, 0, True),         # 512 tokens per tile: two segments of 7 KiB
-    (2100, 16, 64, 8, 30736, 0, True),        # 128 tokens per tile: two segments of 961 and 960 chunks
+    (2100, 16, 64, 8, 30736, 0, True),        # 128 tokens per tile: two segments of 1024 and 897 chunks
+    (1100, 32, 64, 8, 41008, 16, True),       # 64 tokens per tile: three segments
+    (2100, 16, 64, 8, 65536 + 48, 0, True),   # five segments of 832 chunks, the last one shorter
 ]
 
 
@@ -742,7 +744,7 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
         assert not tiled(small, 2048) and not tiled(top1, 2048)
         assert tiled(many, 2048) and tiled(long, 4096)
         assert tiled(many, 15360) and tiled(many, 15376)                # one segment, two segments
-        assert tiled(many, 30720) and not tiled(many, 30736)            # three segments: token walk
+        assert tiled(many, 30736) and tiled(many, 8 * 15360) and not tiled(many, 8 * 15360 + 16)   # up to eight segments
         assert tiled(wide, 3840) and not tiled(wide, 4096)              # segments would be narrower than 4 KiB
         assert not tiled(wide, 16384)
         assert not tiled(many, 14336, 0, fusco.DISPATCH_WIRE) and not tiled(many, 14336, 0, fusco.DISPATCH_TWO_HOP)
