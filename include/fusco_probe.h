@@ -78,6 +78,22 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
 int fusco_probe_dispatch_kernel(int which);
 
 /*
+ * Study and test aid: whether the tiled dispatch pulls a tile's source rows towards the L2 at the start of the
+ * tile (its first workgroups each read one more row and drop it).  0: automatic (on when the source tensor is
+ * taken in one piece).  1: off.  2: on.  which < 0 only reads the setting.  Returns the previous setting,
+ * FUSCO_ERR_INVALID_ARG for which > 2.  The result of fusco_dispatch does not depend on it.
+ */
+int fusco_probe_dispatch_pull(int which);
+
+/*
+ * Study and test aid: how many workgroups of the tiled dispatch a compute unit holds at once.  0: automatic (the
+ * library's choice for the row size).  3 ... 7: that many (the launch asks for dynamic LDS it does not use, which
+ * caps the number).  8: no cap.  wgs < 0 only reads the setting.  Returns the previous setting,
+ * FUSCO_ERR_INVALID_ARG for 1, 2 and values above 8.  The result of fusco_dispatch does not depend on it.
+ */
+int fusco_probe_dispatch_occupancy(int wgs);
+
+/*
  * Study and test aid: the largest source tensor (bytes of x plus its second plane) that fusco_dispatch's
  * tiled mode takes in one piece.  Larger ones are taken in chunks of whole rounds of 8 tiles whose source rows
  * fit this many bytes (at least 8 tiles), each chunk with launches of its own: a sequential read of the chunk's

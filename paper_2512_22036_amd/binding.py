@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_kernel",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_kernel", "fusco_probe_dispatch_occupancy", "fusco_probe_dispatch_pull",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -86,6 +86,10 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.fusco_probe_dispatch_kernel.restype = ctypes.c_int
     lib.fusco_probe_dispatch_kernel.argtypes = [ctypes.c_int]
+    lib.fusco_probe_dispatch_occupancy.restype = ctypes.c_int
+    lib.fusco_probe_dispatch_occupancy.argtypes = [ctypes.c_int]
+    lib.fusco_probe_dispatch_pull.restype = ctypes.c_int
+    lib.fusco_probe_dispatch_pull.argtypes = [ctypes.c_int]
     lib.fusco_probe_source_chunk_bytes.restype = ctypes.c_size_t
     lib.fusco_probe_source_chunk_bytes.argtypes = [sz]
     lib.fusco_probe_time_next_call.restype = ctypes.c_int
@@ -392,6 +396,24 @@ def fusco_probe_dispatch_kernel(which: int = -1) -> int:
     rc = int(load_library().fusco_probe_dispatch_kernel(int(which)))
     if rc < 0:
         _check(rc, "fusco_probe_dispatch_kernel")
+    return rc
+
+
+def fusco_probe_dispatch_occupancy(wgs: int = -1) -> int:
+    """Workgroups of the tiled dispatch per compute unit: 0 automatic, 3 ... 7 that many, 8 no cap; < 0 reads the
+    setting.  Returns the previous setting."""
+    rc = int(load_library().fusco_probe_dispatch_occupancy(int(wgs)))
+    if rc < 0:
+        _check(rc, "fusco_probe_dispatch_occupancy")
+    return rc
+
+
+def fusco_probe_dispatch_pull(which: int = -1) -> int:
+    """Whether the tiled dispatch pulls a tile's source rows towards the L2 at the start of the tile: 0 automatic,
+    1 off, 2 on; < 0 reads the setting.  Returns the previous setting."""
+    rc = int(load_library().fusco_probe_dispatch_pull(int(which)))
+    if rc < 0:
+        _check(rc, "fusco_probe_dispatch_pull")
     return rc
 
 

@@ -202,7 +202,7 @@ int fusco_plan_dispatch(fusco_layout *L, const int32_t *d_topk_idx, const void *
     m.expert_buf = (u32x4 *)d_expert_buf; m.expert_aux = (u32x4 *)d_expert_aux;
     m.send_buf = nullptr; m.send_aux = nullptr;
     m.pair_slot = L->pair_slot; m.pair_send_row = L->pair_send_row; m.pair_first = L->pair_first;
-    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0; m.segs = 1; m.seg_chunks = 0;
+    m.slot_token = nullptr; m.tile_slots = nullptr; m.tile_cap = 0; m.tile_tokens = 0; m.N = L->N; m.segs = 1; m.seg_chunks = 0;
     m.k = L->k;
     m.C = (int32_t)(row_bytes / 16); m.Ca = (int32_t)(aux_row_bytes / 16);
     m.write_expert = 1; m.write_wire = 0;
@@ -225,6 +225,34 @@ static std::atomic<size_t> g_source_chunk_bytes{kSourceChunkBytes};
 // fusco_probe_dispatch_kernel: 0 automatic; 1 keeps fusco_dispatch on the token walk; 2 takes the transfer order
 // wherever its shape allows, whatever the sizes (for comparisons and tests)
 static std::atomic<int> g_dispatch_kernel{0};
+
+// fusco_probe_dispatch_occupancy: workgroups of the tiled dispatch per compute unit; 0 automatic
+static std::atomic<int> g_tiled_occupancy{0};
+
+// fusco_probe_dispatch_pull: 0 automatic, 1 off, 2 on
+static std::atomic<int> g_tiled_pull{0};
+
+// Dynamic LDS that lets exactly `wgs` workgroups share a compute unit's 160 KiB of LDS, which is handed out in
+// 128 blocks of 1280 bytes (3 <= wgs <= 7; the kernels have no LDS of their own); 0 for no cap.
+static size_t lds_for_occupancy(int wgs)
+{
+    if (wgs < 3 || wgs > 7) return 0;
+    return (size_t)(128 / wgs) * 1280;
+}
+
+// Workgroups of the tiled dispatch per compute unit for rows (or column segments) of seg_bytes, source tensor
+// taken in one piece.  The kernel runs at the rate of its writes, which is higher the fewer rows are being
+// written at a time, as long as enough loads stay in flight: measured at 8192 tokens x 8 (dispatch alone, us,
+// source tensor in the memory-side cache, 8 / 7 / 6 / 5 / 4 workgroups): 8 KiB rows 96 / 104 / 108 / 119 / 136,
+// 9 KiB 109 / 107 / 110 / 120 / 135, 12 KiB 138 / 131 / 139 / 148 / 163, 13 KiB 151 / 150 / 146 / 149 / 164,
+// 14 KiB 165 / 164 / 162 / 157 / 171, 15 KiB 173 / 174 / 170 / 164 / 177; two segments of 8 KiB 192 / 203 / 220.
+static int tiled_workgroups_per_cu(size_t seg_bytes, int segs)
+{
+    if (segs > 1 || seg_bytes <= 8192) return 8;
+    if (seg_bytes <= 12288) return 7;
+    if (seg_bytes <= 13312) return 6;
+    return 5;
+}
 
 // Workgroup shape of the tiled dispatch for rows of Ct 16-byte chunks (both planes): the rows are cut into
 // `segs` column segments of `per` chunks, a tile being worked through once per segment, so that the segment
@@ -311,7 +339,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     a.expert_buf = (u32x4 *)d_expert_buf; a.expert_aux = (u32x4 *)d_expert_aux;
     a.send_buf = (u32x4 *)d_send_buf; a.send_aux = (u32x4 *)d_send_aux;
     a.pair_slot = L->pair_slot; a.pair_send_row = L->pair_send_row; a.pair_first = L->pair_first;
-    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0; a.segs = 1; a.seg_chunks = 0;
+    a.slot_token = nullptr; a.tile_slots = nullptr; a.tile_cap = 0; a.tile_tokens = 0; a.N = L->N; a.segs = 1; a.seg_chunks = 0;
     a.k = L->k;
     a.C = (int32_t)(row_bytes / 16);
     a.Ca = (int32_t)(aux_row_bytes / 16);
@@ -331,7 +359,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     // in one XCD's 4 MB L2: the rows are moved tile by tile in transfer order (dispatch_tiled_kernel).
     if (dispatch_in_transfer_order(L, row_bytes, aux_row_bytes, expert, wire, two_hop)) {
         a.slot_token = L->slot_token; a.tile_slots = L->tile_slots;
-        a.tile_cap = L->tile_tokens * L->k;
+        a.tile_cap = L->tile_tokens * L->k; a.tile_tokens = L->tile_tokens;
         tiled_shape(L, Ct, threads, cpt, segs, per);
         a.segs = segs; a.seg_chunks = per;
         // a source tensor that cannot stay in the memory-side cache is taken in chunks of whole rounds of tiles
@@ -348,6 +376,15 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
         if ((uint64_t)((chunk_tiles + kXcds - 1) / kXcds) * (uint64_t)a.tile_cap * (uint64_t)segs * kXcds > 0x7fffffffu)
             return FUSCO_ERR_INVALID_ARG;
         const dim3 tblock((unsigned)threads);
+        // A source tensor that is taken in one piece: its rows are pulled towards the L2 at the start of every tile
+        // and the workgroups per compute unit are capped by the row size.  Taken in chunks (rows already read into
+        // the memory-side cache by touch_kernel) neither helps: 8 KiB rows at 16384 tokens 203 us without a cap,
+        // 274 us with 7 workgroups; 12 KiB segments at 8192 tokens 322 us without the pull, 332 us with it.
+        const int occ_knob = g_tiled_occupancy.load(std::memory_order_relaxed);
+        const int pull_knob = g_tiled_pull.load(std::memory_order_relaxed);
+        const bool pull = pull_knob == 0 ? !chunked : pull_knob == 2;
+        const size_t lds = lds_for_occupancy(occ_knob > 0 ? occ_knob
+                                                          : (chunked ? 8 : tiled_workgroups_per_cu((size_t)per * 16, segs)));
         for (size_t tile0 = 0; tile0 < (size_t)L->tile_count; tile0 += chunk_tiles) {
             const size_t tiles_here = std::min(chunk_tiles, (size_t)L->tile_count - tile0);
             const bool first = tile0 == 0, last = tile0 + tiles_here == (size_t)L->tile_count;
@@ -355,10 +392,10 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
                 const size_t t0 = tile0 * (size_t)L->tile_tokens;
                 const size_t rows = std::min(tiles_here * (size_t)L->tile_tokens, (size_t)L->N - t0);
                 const size_t n = rows * (size_t)a.C, na = rows * (size_t)a.Ca;
-                launch_args(touch_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), s, first ? ev.start : nullptr, (hipEvent_t) nullptr,
+                launch_args(touch_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, first ? ev.start : nullptr, (hipEvent_t) nullptr,
                        a.x + t0 * (size_t)a.C, n);
                 if (na)
-                    launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
+                    launch_args(touch_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, s, (hipEvent_t) nullptr, (hipEvent_t) nullptr,
                            a.x_aux + t0 * (size_t)a.Ca, na);
             }
             const unsigned tblocks = (unsigned)((tiles_here + kXcds - 1) / kXcds) * (unsigned)a.tile_cap * (unsigned)segs * kXcds;
@@ -367,8 +404,10 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
             const dim3 tgrid(tblocks);
 #define FUSCO_TILED(CPT)                                                                              \
     do {                                                                                              \
-        if (a.Ca) launch_args(dispatch_tiled_kernel<CPT, true>, tgrid, tblock, s, e0, e1, a, tb, th); \
-        else launch_args(dispatch_tiled_kernel<CPT, false>, tgrid, tblock, s, e0, e1, a, tb, th);     \
+        if (a.Ca && pull) launch_args(dispatch_tiled_kernel<CPT, true, true>, tgrid, tblock, lds, s, e0, e1, a, tb, th);        \
+        else if (a.Ca) launch_args(dispatch_tiled_kernel<CPT, true, false>, tgrid, tblock, lds, s, e0, e1, a, tb, th);          \
+        else if (pull) launch_args(dispatch_tiled_kernel<CPT, false, true>, tgrid, tblock, lds, s, e0, e1, a, tb, th);          \
+        else launch_args(dispatch_tiled_kernel<CPT, false, false>, tgrid, tblock, lds, s, e0, e1, a, tb, th);                   \
     } while (0)
             switch (cpt) {
             case 1: FUSCO_TILED(1); break;
@@ -683,6 +722,18 @@ int fusco_probe_dispatch_kernel(int which)
 {
     if (which > 2) return FUSCO_ERR_INVALID_ARG;
     return which < 0 ? g_dispatch_kernel.load() : g_dispatch_kernel.exchange(which);
+}
+
+int fusco_probe_dispatch_pull(int which)
+{
+    if (which > 2) return FUSCO_ERR_INVALID_ARG;
+    return which < 0 ? g_tiled_pull.load() : g_tiled_pull.exchange(which);
+}
+
+int fusco_probe_dispatch_occupancy(int wgs)
+{
+    if (wgs > 8 || (wgs > 0 && wgs < 3)) return FUSCO_ERR_INVALID_ARG;
+    return wgs < 0 ? g_tiled_occupancy.load() : g_tiled_occupancy.exchange(wgs);
 }
 
 size_t fusco_probe_source_chunk_bytes(size_t bytes)

@@ -54,12 +54,13 @@ void launch(K kernel, dim3 grid, dim3 block, hipStream_t s, const A &a, hipEvent
     else hipLaunchKernelGGL(kernel, grid, block, 0, s, a);
 }
 
-// the same for kernels with several arguments
+// the same for kernels with several arguments; `lds` bytes of dynamic LDS (which the kernels do not use: asking
+// for it caps the number of workgroups a compute unit holds at once)
 template <typename K, typename... A>
-void launch_args(K kernel, dim3 grid, dim3 block, hipStream_t s, hipEvent_t e0, hipEvent_t e1, A... args)
+void launch_args(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, hipEvent_t e0, hipEvent_t e1, A... args)
 {
-    if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, 0, s, e0, e1, 0, args...);
-    else hipLaunchKernelGGL(kernel, grid, block, 0, s, args...);
+    if (e0 || e1) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, s, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, (unsigned)lds, s, args...);
 }
 
 // Workgroup shape of combine_kernel for rows of C chunks: as many column segments as 1024 threads need, the

@@ -53,6 +53,8 @@ struct DispatchArgs {
     const uint8_t *pair_first;
     const int32_t *slot_token, *tile_slots;   // tiled mode: transfer order of every tile
     int32_t tile_cap;                         // entries per tile in tile_slots
+    int32_t tile_tokens;                      // tokens per tile
+    int32_t N;                                // tokens in all
     int32_t segs;                             // workgroups per row: a row longer than a workgroup covers is cut into columns
     int32_t seg_chunks;                       // 16-byte chunks per column segment (the last one may be shorter)
     int32_t k;
@@ -137,14 +139,18 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 // (store16_through_stream): they do not displace the source rows from the L2 - the fabric counters show
 // every source row fetched 1.03 times, against 1.4 times with plain non-temporal stores - and they go past
 // the memory-side cache, which the next reader of memory would otherwise have to clean first and which so
-// keeps a source tensor that fits it from one call to the next.  Measured on MI355X at 8192 tokens x 8 rows
-// of 14 KiB: 169 us, less than the same stores take without any loads (180 us with plain non-temporal
-// stores): the reads are hidden completely.  The token walk takes 205 us with non-temporal loads and plain
-// stores and 187 us with cached loads and non-temporal stores.
+// keeps a source tensor that fits it from one call to the next.  The reads are hidden completely: the kernel
+// runs at the rate of its write pattern, and that rate goes up when fewer rows are being written at a time.
+// The launch therefore caps the workgroups per compute unit for long rows (tiled_workgroups_per_cu: dynamic LDS
+// that the kernel does not use).  Measured on MI355X at 8192 tokens x 8 rows of 14 KiB, source tensor in the
+// memory-side cache / cold in memory: 8 workgroups per compute unit 164 / 203 us, 5 workgroups 151 / 222 us,
+// 5 workgroups with PULL 157 / 178 us.  The token walk takes 205 us with non-temporal loads and plain stores
+// and 187 us with cached loads and non-temporal stores.
+// PULL: the first tile_tokens workgroups of a pass also read one source row of the tile each (see below).
 // AUX: the second plane exists.  A chunk's source and destination are picked by address selection, not by
 // branching, so that the loads of a thread are issued back to back (a branch per chunk costs 3 % here).
 // The launch covers the tiles [tile_base, tile_base + tiles_here).
-template <int CPT, bool AUX>
+template <int CPT, bool AUX, bool PULL>
 __global__ __launch_bounds__(256) void dispatch_tiled_kernel(DispatchArgs a, uint32_t tile_base, uint32_t tiles_here)
 {
     // a tile is worked through a.segs times, once per column segment of the rows (one pass for rows that a
@@ -157,28 +163,52 @@ __global__ __launch_bounds__(256) void dispatch_tiled_kernel(DispatchArgs a, uin
     if (local >= tiles_here) return;
     const uint32_t tile = tile_base + local;
     const int slot = a.tile_slots[(size_t)tile * a.tile_cap + r];
-    if (slot < 0) return;
-    const int t = a.slot_token[slot];
-    // which segment a pass moves rotates with the token: the segments in use during a pass then lie at different
-    // offsets in their rows, and rows whose size is a power of two do not all fall on the same sets of the L2
-    const uint32_t seg = a.segs > 1 ? (pass + (uint32_t)t) % (uint32_t)a.segs : 0u;
     const int Ct = AUX ? a.C + a.Ca : a.C;
-    const int c_end = min(Ct, (int)(seg + 1) * a.seg_chunks);   // this segment: chunks [seg * seg_chunks, c_end)
-    const int c0 = seg * a.seg_chunks + threadIdx.x;
-    u32x4 v[CPT];
+    // PULL: the first tile_tokens workgroups of a pass also read one source row of the tile each (the segment
+    // of it that this pass moves) and drop it.  All of the tile's source rows are then on their way to the L2
+    // while the tile's first entries are written, instead of every first use of a row waiting for memory in its
+    // own workgroup: with few workgroups per compute unit that wait is what a cold source tensor costs.
+    const int tp = (int)(tile * (uint32_t)a.tile_tokens + r);
+    const bool pull = PULL && r < (uint32_t)a.tile_tokens && tp < a.N;
+    u32x4 p[CPT];
+    const uint32_t pseg = a.segs > 1 ? (pass + (uint32_t)tp) % (uint32_t)a.segs : 0u;
+    const int p_end = min(Ct, (int)(pseg + 1) * a.seg_chunks), p0 = pseg * a.seg_chunks + threadIdx.x;
+    if (pull) {
 #pragma unroll
-    for (int q = 0; q < CPT; ++q) {
-        const int c = c0 + q * blockDim.x;
-        const u32x4 *src = a.x + (size_t)t * a.C + c;
-        if (AUX && c >= a.C) src = a.x_aux + (size_t)t * a.Ca + (c - a.C);
-        if (c < c_end) v[q] = *src;
+        for (int q = 0; q < CPT; ++q) {
+            const int c = p0 + q * blockDim.x;
+            const u32x4 *src = a.x + (size_t)tp * a.C + c;
+            if (AUX && c >= a.C) src = a.x_aux + (size_t)tp * a.Ca + (c - a.C);
+            if (c < p_end) p[q] = *src;
+        }
     }
+    if (slot >= 0) {
+        const int t = a.slot_token[slot];
+        // which segment a pass moves rotates with the token: the segments in use during a pass then lie at different
+        // offsets in their rows, and rows whose size is a power of two do not all fall on the same sets of the L2
+        const uint32_t seg = a.segs > 1 ? (pass + (uint32_t)t) % (uint32_t)a.segs : 0u;
+        const int c_end = min(Ct, (int)(seg + 1) * a.seg_chunks);   // this segment: chunks [seg * seg_chunks, c_end)
+        const int c0 = seg * a.seg_chunks + threadIdx.x;
+        u32x4 v[CPT];
 #pragma unroll
-    for (int q = 0; q < CPT; ++q) {
-        const int c = c0 + q * blockDim.x;
-        u32x4 *dst = a.expert_buf + (size_t)slot * a.C + c;
-        if (AUX && c >= a.C) dst = a.expert_aux + (size_t)slot * a.Ca + (c - a.C);
-        if (c < c_end) store16_through_stream(dst, v[q]);
+        for (int q = 0; q < CPT; ++q) {
+            const int c = c0 + q * blockDim.x;
+            const u32x4 *src = a.x + (size_t)t * a.C + c;
+            if (AUX && c >= a.C) src = a.x_aux + (size_t)t * a.Ca + (c - a.C);
+            if (c < c_end) v[q] = *src;
+        }
+#pragma unroll
+        for (int q = 0; q < CPT; ++q) {
+            const int c = c0 + q * blockDim.x;
+            u32x4 *dst = a.expert_buf + (size_t)slot * a.C + c;
+            if (AUX && c >= a.C) dst = a.expert_aux + (size_t)slot * a.Ca + (c - a.C);
+            if (c < c_end) store16_through_stream(dst, v[q]);
+        }
+    }
+    if (pull) {
+#pragma unroll
+        for (int q = 0; q < CPT; ++q)
+            if (p0 + q * (int)blockDim.x < p_end) asm volatile("" ::"v"(p[q]));   // the value is not used: only the read matters
     }
 }
 

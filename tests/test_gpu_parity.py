@@ -702,6 +702,45 @@ def test_dispatch_in_source_chunks_matches_oracle(fusco, oracle, transfer_order_
     assert np.array_equal(eb.cpu().numpy(), expert_want)
 
 
+@pytest.mark.parametrize("N,k,E,D,row_bytes,aux_bytes,distinct", [TILED_SHAPES[i] for i in (0, 4, 13, 16)])
+def test_tiled_dispatch_study_knobs_do_not_change_the_result(fusco, oracle, transfer_order_everywhere, N, k, E, D, row_bytes,
+                                                             aux_bytes, distinct):
+    """Workgroups per compute unit (a launch with unused dynamic LDS) and the pull of a tile's source rows at the start
+    of the tile are choices of speed: every setting gives the oracle's expert tensor.  Shapes: a ragged last tile, a
+    second plane, two and three column segments."""
+    rng = np.random.default_rng(N + row_bytes + 7)
+    A = random_topk(rng, N, k, E, distinct)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    xa = rng.integers(0, 256, size=(N, aux_bytes), dtype=np.uint8) if aux_bytes else None
+    want = oracle.plan(A, E, D)
+    L, _ = gpu_plan(fusco, A, E, D)
+    assert fusco.fusco_dispatch_in_transfer_order(L, row_bytes, aux_bytes)
+    if aux_bytes:
+        _, expert_want, _, eaux_want = oracle.dispatch(want, x, xa)
+    else:
+        _, expert_want = oracle.dispatch(want, x)
+    assert fusco.fusco_probe_dispatch_occupancy() == 0 and fusco.fusco_probe_dispatch_pull() == 0
+    try:
+        for occupancy in (3, 5, 7, 8):
+            for pull in (1, 2):
+                fusco.fusco_probe_dispatch_occupancy(occupancy)
+                fusco.fusco_probe_dispatch_pull(pull)
+                eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+                ea = torch.full((L.P, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda") if aux_bytes else None
+                fusco.fusco_dispatch(L, dev(x), eb, x_aux=dev(xa) if aux_bytes else None, expert_aux=ea)
+                torch.cuda.synchronize()
+                assert np.array_equal(eb.cpu().numpy(), expert_want), (occupancy, pull)
+                assert not aux_bytes or np.array_equal(ea.cpu().numpy(), eaux_want), (occupancy, pull)
+    finally:
+        fusco.fusco_probe_dispatch_occupancy(0)
+        fusco.fusco_probe_dispatch_pull(0)
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_probe_dispatch_occupancy(2)
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_probe_dispatch_pull(3)
+    assert fusco.fusco_probe_dispatch_occupancy() == 0 and fusco.fusco_probe_dispatch_pull() == 0
+
+
 def test_dispatch_in_transfer_order_skips_invalid_ids(fusco, oracle, transfer_order_everywhere):
     rng = np.random.default_rng(5)
     N, k, E, D, row_bytes = 5000, 8, 64, 8, 1024
