@@ -376,15 +376,18 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
         if ((uint64_t)((chunk_tiles + kXcds - 1) / kXcds) * (uint64_t)a.tile_cap * (uint64_t)segs * kXcds > 0x7fffffffu)
             return FUSCO_ERR_INVALID_ARG;
         const dim3 tblock((unsigned)threads);
-        // A source tensor that is taken in one piece: its rows are pulled towards the L2 at the start of every tile
-        // and the workgroups per compute unit are capped by the row size.  Taken in chunks (rows already read into
-        // the memory-side cache by touch_kernel) neither helps: 8 KiB rows at 16384 tokens 203 us without a cap,
-        // 274 us with 7 workgroups; 12 KiB segments at 8192 tokens 322 us without the pull, 332 us with it.
+        // A source tensor that is taken in one piece has its rows pulled towards the L2 at the start of every tile;
+        // taken in chunks, touch_kernel has just read them and the pull only costs (12 KiB segments at 8192 tokens:
+        // 322 us without it, 332 us with it).  The workgroups per compute unit are capped by the row size only while
+        // the source tensor and an output of its size stay in the memory-side cache from step to step.  Measured
+        // with 14 KiB rows, dispatch alone, 8 / 5 workgroups: 8192 tokens (112 MiB) 164 / 155 us, 8704 tokens
+        // (119 MiB) 191 / 188 us, 9216 tokens (126 MiB) 205 / 250 us, 32768 tokens without chunks 793 / 923 us.
         const int occ_knob = g_tiled_occupancy.load(std::memory_order_relaxed);
         const int pull_knob = g_tiled_pull.load(std::memory_order_relaxed);
         const bool pull = pull_knob == 0 ? !chunked : pull_knob == 2;
-        const size_t lds = lds_for_occupancy(occ_knob > 0 ? occ_knob
-                                                          : (chunked ? 8 : tiled_workgroups_per_cu((size_t)per * 16, segs)));
+        const int wgs = occ_knob > 0 ? occ_knob
+                        : (source_bytes <= kResidentSourceBytes ? tiled_workgroups_per_cu((size_t)per * 16, segs) : 8);
+        const size_t lds = lds_for_occupancy(wgs);
         for (size_t tile0 = 0; tile0 < (size_t)L->tile_count; tile0 += chunk_tiles) {
             const size_t tiles_here = std::min(chunk_tiles, (size_t)L->tile_count - tile0);
             const bool first = tile0 == 0, last = tile0 + tiles_here == (size_t)L->tile_count;

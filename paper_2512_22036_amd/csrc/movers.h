@@ -68,6 +68,7 @@ constexpr size_t kTiledMaxTileBytes = (size_t)3840 << 10; // source rows of one 
 constexpr size_t kSourceChunkBytes = (size_t)128 << 20;   // source rows of one chunk: half the 256 MB memory-side cache
 constexpr size_t kCacheBytes = (size_t)256 << 20;         // the memory-side cache
 constexpr size_t kTiledShortRowBytes = 8192;              // rows below this are tiled only with a small source tensor
+constexpr size_t kResidentSourceBytes = (size_t)116 << 20; // largest source tensor that stays in that cache next to an output of its size
 
 // STREAM: the rows are written with non-temporal stores, which go past the memory-side cache (measured: a
 // read that follows such a write runs at the cold rate, 5.7 TB/s for 256 MB, instead of 4.2 TB/s on rows
