@@ -186,9 +186,10 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
  * rows of one tile (tile_tokens * (row_bytes + aux_row_bytes)) fit the 4 MB L2 of an XCD whole (at most
  * 3840 KiB) or cut into up to eight column segments of at least 4 KiB each, which are then moved in as many
  * passes over the tile; and when the sizes make it pay: the expert tensor is larger than the 256 MB memory-side cache
- * (a smaller one is left there by the token walk's plain stores for its reader), and rows shorter than 8 KiB
- * come with a source tensor of at most 128 MiB (less than 128 MiB for rows shorter than 4 KiB).  Both ways
- * write the same bytes.
+ * (a smaller one is left there by the token walk's plain stores for its reader), rows shorter than 8 KiB
+ * come with a source tensor of at most 128 MiB (less than 128 MiB for rows shorter than 4 KiB), and a source
+ * tensor of more than 128 MiB comes with k >= 8, or with k >= 5 and rows that need no column segments.  Both
+ * ways write the same bytes.
  */
 int fusco_dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, size_t aux_row_bytes, uint32_t flags);
 

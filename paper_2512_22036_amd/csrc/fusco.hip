@@ -291,12 +291,18 @@ static bool dispatch_in_transfer_order(const fusco_layout *L, size_t row_bytes, 
     // - an expert tensor that fits the memory-side cache: the walk's plain stores leave it there for its reader;
     // - rows shorter than 8 KiB together with a source tensor that would be taken in chunks (more than 128 MiB),
     //   and rows shorter than 4 KiB already with one of 128 MiB, which does not stay in that cache next to the
-    //   output of a combine of the same size: the tiles' short runs then lose to the walk.
+    //   output of a combine of the same size: the tiles' short runs then lose to the walk;
+    // - fewer than 8 rows per token together with a source tensor of more than 128 MiB: a source row is then
+    //   fetched for few uses, and the tiles lose to the walk with 4 rows per token (282 against 218 us at 32768
+    //   tokens of 7 KiB, 209 against 177 us at 16384 tokens of 12 KiB) and with 5 or 6 rows per token when the rows
+    //   are moved in column segments (358 against 303 us at 16384 tokens of 14 KiB, 6 rows per token); whole rows
+    //   of 8-10 KiB with 5 or 6 rows per token come out even or up to 2 % ahead in the step.
     const size_t row = row_bytes + aux_row_bytes, source = (size_t)L->N * row;
     const size_t limit = g_source_chunk_bytes.load(std::memory_order_relaxed);
     if ((size_t)L->P * row <= kCacheBytes) return false;
     if (row < kTiledShortRowBytes && source > limit) return false;
     if (row < kTiledShortRowBytes / 2 && source >= limit) return false;
+    if (source > limit && !(L->k >= 8 || (L->k >= 5 && segs == 1))) return false;
     return true;
 }
 

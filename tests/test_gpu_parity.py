@@ -777,6 +777,11 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
     assert tiled(long, 2032) and not tiled(long, 2048) and not tiled(long, 4096) and tiled(long, 8192)
     half = fusco.Layout(32768, 8, 256, 8)
     assert tiled(half, 4096) and not tiled(half, 4112) and tiled(half, 2048)       # 128 MiB of source rows, just more, half
+    # a source tensor of more than 128 MiB: only with 8 rows per token, or 5 and more when the rows need no segments
+    four, six = fusco.Layout(32768, 4, 128, 8), fusco.Layout(32768, 6, 128, 8)
+    assert not tiled(four, 8192) and not tiled(four, 12288) and tiled(fusco.Layout(8192, 4, 128, 8), 12288)
+    assert tiled(six, 8192) and tiled(six, 10240) and not tiled(six, 14336)       # 341 tokens per tile: 14 KiB rows take two segments
+    assert tiled(long, 16384) and tiled(fusco.Layout(16384, 6, 128, 8), 7168)     # k = 8 with segments; 112 MiB of source rows
     assert fusco.fusco_probe_dispatch_kernel(2) == 0
     try:
         # workgroup shapes: the whole tile's source rows, or two column segments of them, must fit an XCD's L2
