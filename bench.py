@@ -641,10 +641,13 @@ def main() -> int:
         if fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes, 0):
             try:
                 fusco.fusco_probe_dispatch_kernel(1)
-                token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x),
-                              "streaming_stores": source_case(lambda: None, lambda i: d_x, fusco.DISPATCH_STREAMING)}
+                fusco.fusco_probe_dispatch_walk(1)      # non-temporal loads, plain stores
+                token_walk = {"plain_stores": source_case(lambda: None, lambda i: d_x)}
+                fusco.fusco_probe_dispatch_walk(0)      # the library's choice for these sizes (cached loads, streaming stores)
+                token_walk["streaming_stores"] = source_case(lambda: None, lambda i: d_x)
             finally:
                 fusco.fusco_probe_dispatch_kernel(0)
+                fusco.fusco_probe_dispatch_walk(0)
         # a layer's other traffic between two shuffles (weights, attention) leaves nothing of the previous step in the
         # memory-side cache: 1 GiB of another buffer is read before x is rewritten
         d_other = torch.empty((1 << 30) // 16384, 16384, dtype=torch.uint8, device="cuda")

@@ -171,9 +171,10 @@ int fusco_plan_static(fusco_layout *L, const int32_t *d_topk_idx, void *stream);
  * the extra pass costs U + P more row reads.
  * FUSCO_DISPATCH_STREAMING may be added to the fused modes (not to FUSCO_DISPATCH_TWO_HOP): the token walk then
  * writes its rows with non-temporal stores, which do not stay in the GPU's 256 MB memory-side cache (the
- * transfer order always writes that way).  Choose it when other traffic (an expert computation) comes between
- * this call and the first reader of the rows: a plain dispatch leaves its last ~200 MB of rows dirty in that
- * cache, and whoever streams through memory next pays for writing them back.  Results are identical either way.
+ * transfer order always writes that way, and so does the token walk on its own when the tensors it writes
+ * exceed that cache).  Choose it for smaller tensors when other traffic (an expert computation) comes between
+ * this call and the first reader of the rows: a plain dispatch leaves its rows dirty in that cache, and whoever
+ * streams through memory next pays for writing them back.  Results are identical either way.
  */
 int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, const void *d_x_aux,
                    size_t aux_row_bytes, void *d_expert_buf, void *d_expert_aux, void *d_send_buf,

@@ -78,6 +78,17 @@ int fusco_probe_consume_slices(const void *d_stream, uint64_t total_bytes, uint6
 int fusco_probe_dispatch_kernel(int which);
 
 /*
+ * Study and test aid: loads and stores of fusco_dispatch's token walk.  0: automatic (plain stores and
+ * non-temporal loads while the tensors it writes fit the 256 MB memory-side cache and FUSCO_DISPATCH_STREAMING
+ * is not given; otherwise non-temporal stores, with cached loads for a source tensor of up to 128 MiB and
+ * non-temporal loads for a larger one).  1: non-temporal loads, plain stores.  2: cached loads, plain stores.
+ * 3: non-temporal loads and stores.  4: cached loads, non-temporal stores.  which < 0 only reads the setting.
+ * Returns the previous setting, FUSCO_ERR_INVALID_ARG for which > 4.  The result of fusco_dispatch does not
+ * depend on it.
+ */
+int fusco_probe_dispatch_walk(int which);
+
+/*
  * Study and test aid: whether the tiled dispatch pulls a tile's source rows towards the L2 at the start of the
  * tile (its first workgroups each read one more row and drop it).  0: automatic (on when the source tensor is
  * taken in one piece).  1: off.  2: on.  which < 0 only reads the setting.  Returns the previous setting,

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfusco.so")
 
 EXPORTS = ("fusco_version", "fusco_status_string", "fusco_layout_bytes", "fusco_scratch_bytes",
-           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_kernel", "fusco_probe_dispatch_occupancy", "fusco_probe_dispatch_pull",
+           "fusco_layout_bind", "fusco_plan", "fusco_plan_static", "fusco_dispatch", "fusco_dispatch_in_transfer_order", "fusco_combine", "fusco_plan_dispatch", "fusco_probe_copy", "fusco_probe_rows", "fusco_probe_pieces", "fusco_probe_consume_slices", "fusco_probe_time_next_call", "fusco_probe_source_chunk_bytes", "fusco_probe_dispatch_kernel", "fusco_probe_dispatch_occupancy", "fusco_probe_dispatch_pull", "fusco_probe_dispatch_walk",
            "fusco_combine_two_hop", "fusco_balance_groups", "fusco_cross_node_load", "fusco_segments_scan", "fusco_segments_copy",
            "fusco_disaggregated_plan", "fusco_disaggregated_dispatch", "fusco_disaggregated_combine")
 
@@ -88,6 +88,8 @@ def load_library() -> ctypes.CDLL:
     lib.fusco_probe_dispatch_kernel.argtypes = [ctypes.c_int]
     lib.fusco_probe_dispatch_occupancy.restype = ctypes.c_int
     lib.fusco_probe_dispatch_occupancy.argtypes = [ctypes.c_int]
+    lib.fusco_probe_dispatch_walk.restype = ctypes.c_int
+    lib.fusco_probe_dispatch_walk.argtypes = [ctypes.c_int]
     lib.fusco_probe_dispatch_pull.restype = ctypes.c_int
     lib.fusco_probe_dispatch_pull.argtypes = [ctypes.c_int]
     lib.fusco_probe_source_chunk_bytes.restype = ctypes.c_size_t
@@ -405,6 +407,16 @@ def fusco_probe_dispatch_occupancy(wgs: int = -1) -> int:
     rc = int(load_library().fusco_probe_dispatch_occupancy(int(wgs)))
     if rc < 0:
         _check(rc, "fusco_probe_dispatch_occupancy")
+    return rc
+
+
+def fusco_probe_dispatch_walk(which: int = -1) -> int:
+    """Loads and stores of the token walk: 0 automatic, 1 non-temporal loads + plain stores, 2 cached loads + plain
+    stores, 3 non-temporal loads and stores, 4 cached loads + non-temporal stores; < 0 reads the setting.  Returns the
+    previous setting."""
+    rc = int(load_library().fusco_probe_dispatch_walk(int(which)))
+    if rc < 0:
+        _check(rc, "fusco_probe_dispatch_walk")
     return rc
 
 

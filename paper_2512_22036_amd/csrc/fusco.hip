@@ -229,6 +229,9 @@ static std::atomic<int> g_dispatch_kernel{0};
 // fusco_probe_dispatch_occupancy: workgroups of the tiled dispatch per compute unit; 0 automatic
 static std::atomic<int> g_tiled_occupancy{0};
 
+// fusco_probe_dispatch_walk: 0 automatic; 1 + (bit 0 cached loads, bit 1 non-temporal stores)
+static std::atomic<int> g_walk_mode{0};
+
 // fusco_probe_dispatch_pull: 0 automatic, 1 off, 2 on
 static std::atomic<int> g_tiled_pull{0};
 
@@ -430,18 +433,33 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
     if ((uint64_t)L->N * (uint64_t)segs > 0x7fffffffu) return FUSCO_ERR_INVALID_ARG;
     a.segs = segs; a.seg_chunks = per;
     const dim3 grid((unsigned)L->N * (unsigned)segs), block((unsigned)threads);
-    if (streaming) {
+    {
+        // Loads and stores of the walk (dispatch_kernel's MODE).  Tensors of more than 256 MB in all cannot stay in
+        // the memory-side cache for their reader, and what plain stores leave of them there dirty only slows the
+        // next reader of memory down: they are written with non-temporal stores, as with FUSCO_DISPATCH_STREAMING.
+        // Measured in a dispatch + combine loop whose combine reads another tensor, plain / streaming, % of peak:
+        // 8192 tokens x 8 rows of 14 KiB 67.0 / 74.8, 16384 x 8 x 4 KiB 66.7 / 76.3, 32768 x 2 x 8 KiB 75.0 / 81.9,
+        // 32768 x 4 x 14 KiB 68.6 / 70.5, 65536 x 1 x 8 KiB 73.5 / 75.4; with the combine reading the rows just
+        // written 73.7 / 74.6, 71.1 / 76.2, 76.8 / 77.8, 70.0 / 70.3, 73.4 / 74.8.
+        const size_t row = row_bytes + aux_row_bytes;
+        const size_t written = ((expert && !two_hop ? (size_t)L->P : 0) + (wire ? (size_t)L->send_cap : 0)) * row;
+        const bool stream_stores = streaming || (!two_hop && written > kCacheBytes);   // the second hop reads the rows at once
+        const bool cached_loads = stream_stores && (size_t)L->N * row <= g_source_chunk_bytes.load(std::memory_order_relaxed);
+        const int knob = g_walk_mode.load(std::memory_order_relaxed);
+        const int mode = knob > 0 ? knob - 1 : (stream_stores ? 2 : 0) + (cached_loads ? 1 : 0);
+#define FUSCO_WALK(CPT)                                                                       \
+    switch (mode) {                                                                           \
+    case 0: launch(dispatch_kernel<CPT, 0>, grid, block, s, a, ev.start, ev.stop); break;     \
+    case 1: launch(dispatch_kernel<CPT, 1>, grid, block, s, a, ev.start, ev.stop); break;     \
+    case 2: launch(dispatch_kernel<CPT, 2>, grid, block, s, a, ev.start, ev.stop); break;     \
+    default: launch(dispatch_kernel<CPT, 3>, grid, block, s, a, ev.start, ev.stop); break;    \
+    }
         switch (cpt) {
-        case 1: launch(dispatch_kernel<1, true>, grid, block, s, a, ev.start, ev.stop); break;
-        case 2: launch(dispatch_kernel<2, true>, grid, block, s, a, ev.start, ev.stop); break;
-        default: launch(dispatch_kernel<4, true>, grid, block, s, a, ev.start, ev.stop); break;
+        case 1: FUSCO_WALK(1); break;
+        case 2: FUSCO_WALK(2); break;
+        default: FUSCO_WALK(4); break;
         }
-    } else {
-        switch (cpt) {
-        case 1: launch(dispatch_kernel<1>, grid, block, s, a, ev.start, ev.stop); break;
-        case 2: launch(dispatch_kernel<2>, grid, block, s, a, ev.start, ev.stop); break;
-        default: launch(dispatch_kernel<4>, grid, block, s, a, ev.start, ev.stop); break;
-        }
+#undef FUSCO_WALK
     }
     if (two_hop) {
         // second hop: every row of the expert tensor is pulled from its token's row in the receive
@@ -731,6 +749,12 @@ int fusco_probe_dispatch_kernel(int which)
 {
     if (which > 2) return FUSCO_ERR_INVALID_ARG;
     return which < 0 ? g_dispatch_kernel.load() : g_dispatch_kernel.exchange(which);
+}
+
+int fusco_probe_dispatch_walk(int which)
+{
+    if (which > 4) return FUSCO_ERR_INVALID_ARG;
+    return which < 0 ? g_walk_mode.load() : g_walk_mode.exchange(which);
 }
 
 int fusco_probe_dispatch_pull(int which)

@@ -70,12 +70,14 @@ constexpr size_t kCacheBytes = (size_t)256 << 20;         // the memory-side cac
 constexpr size_t kTiledShortRowBytes = 8192;              // rows below this are tiled only with a small source tensor
 constexpr size_t kResidentSourceBytes = (size_t)116 << 20; // largest source tensor that stays in that cache next to an output of its size
 
-// STREAM: the rows are written with non-temporal stores, which go past the memory-side cache (measured: a
-// read that follows such a write runs at the cold rate, 5.7 TB/s for 256 MB, instead of 4.2 TB/s on rows
-// that sit dirty in that cache), and the source row is read with a plain cached load instead of a
-// non-temporal one: a source tensor that fits the memory-side cache then stays there from one call to the
-// next, since nothing this kernel writes displaces it (187 us instead of 208 us at 8192 tokens x 8 rows of
-// 14 KiB; non-temporal loads together with non-temporal stores are the worst pairing, 215 us).
+// Loads and stores of the token walk (MODE of dispatch_kernel: bit 0 cached loads, bit 1 non-temporal stores).
+// Non-temporal stores go past the memory-side cache (a read that follows such a write runs at the cold rate,
+// 5.7 TB/s for 256 MB, instead of 4.2 TB/s on rows that sit dirty in that cache); plain stores leave the rows
+// there, which is what a reader of a tensor of up to 256 MB wants.  With non-temporal stores a source tensor
+// that fits that cache is read with plain cached loads and stays there from one call to the next, since
+// nothing the kernel writes displaces it (8192 tokens x 8 rows of 14 KiB: 187 us instead of 208 us; non-temporal
+// loads together with non-temporal stores take 215 us there); a larger one is read with non-temporal loads
+// (32768 tokens x 2 rows of 8 KiB: 138 us, against 168 us with cached loads).  walk_mode in fusco.hip chooses.
 template <bool STREAM>
 __device__ __forceinline__ void put16(u32x4 *p, u32x4 v)
 {
@@ -83,7 +85,7 @@ __device__ __forceinline__ void put16(u32x4 *p, u32x4 v)
     else *p = v;
 }
 
-template <int CPT, bool STREAM = false>
+template <int CPT, int MODE = 0>   // MODE bit 0: cached loads, bit 1: non-temporal stores
 __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
 {
     // workgroup = (token, column segment), segments of one row next to each other in launch order, so that a
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
     for (int i = 0; i < CPT; ++i) {
         const int c = c0 + i * blockDim.x;
         const u32x4 *src = c < a.C ? a.x + (size_t)t * a.C + c : a.x_aux + (size_t)t * a.Ca + (c - a.C);
-        if (c < c_end) v[i] = STREAM ? *src : load16_stream(src);
+        if (c < c_end) v[i] = (MODE & 1) ? *src : load16_stream(src);
     }
     const int32_t *slots = a.pair_slot + (size_t)t * a.k;
     if (a.write_expert) {
@@ -108,8 +110,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
                 if (c >= c_end) continue;
-                if (c < a.C) put16<STREAM>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
-                else put16<STREAM>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
+                if (c < a.C) put16<(MODE & 2) != 0>(a.expert_buf + (size_t)slot * a.C + c, v[i]);
+                else put16<(MODE & 2) != 0>(a.expert_aux + (size_t)slot * a.Ca + (c - a.C), v[i]);
             }
         }
     }
@@ -123,8 +125,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a)
             for (int i = 0; i < CPT; ++i) {
                 const int c = c0 + i * blockDim.x;
                 if (c >= c_end) continue;
-                if (c < a.C) put16<STREAM>(a.send_buf + (size_t)row * a.C + c, v[i]);
-                else put16<STREAM>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
+                if (c < a.C) put16<(MODE & 2) != 0>(a.send_buf + (size_t)row * a.C + c, v[i]);
+                else put16<(MODE & 2) != 0>(a.send_aux + (size_t)row * a.Ca + (c - a.C), v[i]);
             }
         }
     }

@@ -245,6 +245,8 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_dispatch_occupancy(-1) == 5 and lib.fusco_probe_dispatch_occupancy(8) == 5
     assert lib.fusco_probe_dispatch_occupancy(2) == -1 and lib.fusco_probe_dispatch_occupancy(9) == -1     # 1, 2 and > 8 refused
     assert lib.fusco_probe_dispatch_occupancy(0) == 8 and lib.fusco_probe_dispatch_occupancy(-1) == 0
+    assert lib.fusco_probe_dispatch_walk(-1) == 0 and lib.fusco_probe_dispatch_walk(4) == 0
+    assert lib.fusco_probe_dispatch_walk(5) == -1 and lib.fusco_probe_dispatch_walk(0) == 4 and lib.fusco_probe_dispatch_walk(-1) == 0
     assert lib.fusco_probe_dispatch_pull(-1) == 0 and lib.fusco_probe_dispatch_pull(2) == 0
     assert lib.fusco_probe_dispatch_pull(1) == 2 and lib.fusco_probe_dispatch_pull(3) == -1
     assert lib.fusco_probe_dispatch_pull(0) == 1 and lib.fusco_probe_dispatch_pull(-1) == 0

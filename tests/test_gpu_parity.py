@@ -797,6 +797,37 @@ def test_dispatch_chooses_the_token_walk_where_the_transfer_order_does_not_pay(f
         assert fusco.fusco_probe_dispatch_kernel(0) == 2
 
 
+@pytest.mark.parametrize("which", [1, 2, 3, 4])
+def test_token_walk_loads_and_stores_do_not_change_the_result(fusco, oracle, which):
+    """Non-temporal or cached loads, plain or non-temporal stores of the token walk (the library picks by the sizes of
+    the tensors): the expert tensor, the wire tensor and their second planes are the oracle's with every pairing.
+    Rows of 1153 chunks with the second plane: two column segments per token."""
+    rng = np.random.default_rng(500 + which)
+    N, k, E, D, row_bytes, aux_bytes = 700, 6, 48, 8, 18416, 32
+    A = random_topk(rng, N, k, E)
+    x = rng.integers(0, 256, size=(N, row_bytes), dtype=np.uint8)
+    xa = rng.integers(0, 256, size=(N, aux_bytes), dtype=np.uint8)
+    want = oracle.plan(A, E, D)
+    L, _ = gpu_plan(fusco, A, E, D)
+    eb = torch.full((L.P, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    ea = torch.full((L.P, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    sb = torch.full((L.send_cap, row_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    sa = torch.full((L.send_cap, aux_bytes), 0xEE, dtype=torch.uint8, device="cuda")
+    assert fusco.fusco_probe_dispatch_walk(which) == 0
+    try:
+        fusco.fusco_dispatch(L, dev(x), eb, x_aux=dev(xa), expert_aux=ea, send_buf=sb, send_aux=sa, flags=3)
+        torch.cuda.synchronize()
+    finally:
+        assert fusco.fusco_probe_dispatch_walk(0) == which
+    send_want, expert_want, saux_want, eaux_want = oracle.dispatch(want, x, xa)
+    U = want.U
+    assert np.array_equal(eb.cpu().numpy(), expert_want) and np.array_equal(ea.cpu().numpy(), eaux_want)
+    assert np.array_equal(sb.cpu().numpy()[:U], send_want) and np.array_equal(sa.cpu().numpy()[:U], saux_want)
+    assert np.all(sb.cpu().numpy()[U:] == 0xEE)
+    with pytest.raises(fusco.FuscoError):
+        fusco.fusco_probe_dispatch_walk(5)
+
+
 def test_dispatch_kept_on_the_token_walk_gives_the_same_rows(fusco, oracle):
     """The study knob that keeps fusco_dispatch on the token walk changes the kernel, not the result."""
     rng = np.random.default_rng(77)
