@@ -72,6 +72,12 @@ inline void combine_shape(int C, int &threads, int &segs)
     threads = round_up((C + segs - 1) / segs, kWave);
 }
 
+// Rows that a thread of combine_kernel has in flight at a time (JU).  Inputs that are bound by memory run a few
+// percent faster with two than with all eight of a token's rows (8192 tokens x 8 rows of 14 KiB: 172 us against
+// 178 us; 4096 tokens: 88 against 92 us; 32768 x 8 x 2 KiB: 95 against 97 us; 8 KiB rows: the same); small inputs
+// are bound by latency and take the token's rows at once.
+constexpr size_t kCombineLatencyBoundBytes = (size_t)64 << 20;
+
 template <bool Y_BF16, bool OUT_BF16>
 void launch_combine(CombineArgs a, int N, hipStream_t s, hipEvent_t e0, hipEvent_t e1)
 {
@@ -79,7 +85,10 @@ void launch_combine(CombineArgs a, int N, hipStream_t s, hipEvent_t e0, hipEvent
     combine_shape(a.C, threads, a.segs);
     a.n_rows = N;
     const dim3 grid((unsigned)N * (unsigned)a.segs), block((unsigned)threads);
-    launch(combine_kernel<Y_BF16, OUT_BF16, 1, 8>, grid, block, s, a, e0, e1);
+    if ((size_t)N * (size_t)a.k * (size_t)a.C * 16 < kCombineLatencyBoundBytes)
+        launch(combine_kernel<Y_BF16, OUT_BF16, 1, 8>, grid, block, s, a, e0, e1);
+    else
+        launch(combine_kernel<Y_BF16, OUT_BF16, 1, 2>, grid, block, s, a, e0, e1);
 }
 
 // dst[r] = src[index(r)] for n_rows destination rows of C chunks (see gather_rows_kernel)

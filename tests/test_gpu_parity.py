@@ -418,6 +418,28 @@ def test_combine_f32_input_matches_oracle(fusco, oracle, N, k, E, D, H, out_dtyp
     _combine_case(fusco, oracle, A, E, D, y, w, out_dtype)
 
 
+# inputs of 64 MiB and more take the token's rows two at a time instead of all at once: odd k, a k that is not a
+# multiple of the group, the largest k, two column segments, fp32 input
+COMBINE_SHAPES_TWO_ROWS_IN_FLIGHT = [
+    # N, k, E, D, H, y is fp32
+    (3000, 5, 20, 4, 2304, False), (6000, 3, 6, 3, 2304, False), (600, 64, 128, 8, 1024, False),
+    (1200, 8, 32, 4, 8 * 1285, False), (2500, 7, 14, 2, 1024, True), (9000, 1, 4, 2, 4096, False),
+]
+
+
+@pytest.mark.parametrize("N,k,E,D,H,y_f32", COMBINE_SHAPES_TWO_ROWS_IN_FLIGHT)
+@pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
+def test_combine_of_memory_bound_sizes_matches_oracle(fusco, oracle, N, k, E, D, H, y_f32, out_dtype):
+    assert N * k * H * (4 if y_f32 else 2) >= 64 << 20
+    rng = np.random.default_rng(N * H + k + 2)
+    A = random_topk(rng, N, k, E)
+    y = rng.standard_normal((N * k, H)).astype(np.float32)
+    if not y_f32:
+        y = W.bf16_bits(y)
+    w = (rng.standard_normal((N, k)) * 2).astype(np.float32)
+    _combine_case(fusco, oracle, A, E, D, y, w, out_dtype)
+
+
 @pytest.mark.parametrize("out_dtype", [torch.bfloat16, torch.float32])
 def test_combine_special_values(fusco, oracle, out_dtype):
     """Zeros of both signs, subnormals, the largest finite values, infinities and NaNs in y, and weights that
