@@ -386,6 +386,67 @@ def token_sweep(fusco, torch, np, W, reps=20):
     return {"row_bytes": base.row_bytes, "k": base.k, "E": base.E, "reps": reps, "sizes": rows}
 
 
+def shape_sweep(fusco, torch, np, W, reps=16):
+    """Dispatch and combine for other MoE shapes (rows per token, experts, row size, token count), with fusco_dispatch
+    on the token walk, on the transfer order where its workgroup shape allows, and as the library chooses: the
+    evidence for the choice rules.  The combine reads the tensor dispatch wrote; per-call kernel times."""
+    from dataclasses import replace
+    base = W.get_config("dsv3")
+    shapes = [  # name, N, hidden, k, E
+        ("dsv3", 8192, 7168, 8, 256), ("dsv3, 1024 experts", 8192, 7168, 8, 1024), ("dsv3, 64 experts", 8192, 7168, 8, 64),
+        ("top-6 of 160, 10 KiB rows", 8192, 5120, 6, 160), ("top-4 of 128, 12 KiB rows", 8192, 6144, 4, 128),
+        ("top-4 of 128, 6 KiB rows", 16384, 3072, 4, 128), ("top-4 of 32, 5.6 KiB rows", 8192, 2880, 4, 32),
+        ("top-2 of 8, 8 KiB rows", 16384, 4096, 2, 8),
+        ("top-8, 8 KiB rows, x 256 MiB", 32768, 4096, 8, 128), ("top-8, 14 KiB rows, x 224 MiB", 16384, 7168, 8, 128),
+        ("top-6, 8 KiB rows, x 256 MiB", 32768, 4096, 6, 128), ("top-6, 10 KiB rows, x 240 MiB", 24576, 5120, 6, 128),
+        ("top-6, 14 KiB rows, x 224 MiB", 16384, 7168, 6, 128), ("top-5, 10 KiB rows, x 240 MiB", 24576, 5120, 5, 128),
+        ("top-4, 7 KiB rows, x 224 MiB", 32768, 3584, 4, 128), ("top-4, 12 KiB rows, x 192 MiB", 16384, 6144, 4, 128),
+        ("top-4, 14 KiB rows, x 448 MiB", 32768, 7168, 4, 128), ("top-2, 8 KiB rows, x 256 MiB", 32768, 4096, 2, 8),
+    ]
+    rows = []
+    for name, N, H, k, E in shapes:
+        cfg = replace(base, N=N, H=H, k=k, E=E, D=8)
+        A, w = W.make_routing(cfg)
+        d_A, d_w = torch.from_numpy(A).cuda(), torch.from_numpy(w).cuda()
+        L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+        fusco.fusco_plan(L, d_A)
+        x = torch.randn((cfg.N, cfg.H), device="cuda").to(torch.bfloat16)
+        eb = torch.empty((cfg.P, cfg.H), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty((cfg.N, cfg.H), dtype=torch.bfloat16, device="cuda")
+        nb = (cfg.N + cfg.P) * cfg.row_bytes
+        row = {"name": name, "N": N, "hidden": H, "k": k, "E": E, "source_MiB": N * cfg.row_bytes / 2**20,
+               "expert_tensor_MiB": cfg.P * cfg.row_bytes / 2**20,
+               "library_takes_transfer_order": bool(fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes))}
+        try:
+            for label, which in (("token_walk", 1), ("transfer_order", 2)):
+                fusco.fusco_probe_dispatch_kernel(which)
+                if which == 2 and not fusco.fusco_dispatch_in_transfer_order(L, cfg.row_bytes):
+                    row[label] = None        # the workgroup shape does not allow it
+                    continue
+                ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(reps)]
+                for r in ev:
+                    for e in r:
+                        e.record()
+                for _ in range(40):
+                    fusco.fusco_dispatch(L, x, eb)
+                    fusco.fusco_combine(L, eb, d_w, out)
+                torch.cuda.synchronize()
+                for i in range(reps):
+                    fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
+                    fusco.fusco_dispatch(L, x, eb)
+                    fusco.fusco_probe_time_next_call(ev[i][2], ev[i][3])
+                    fusco.fusco_combine(L, eb, d_w, out)
+                torch.cuda.synchronize()
+                d = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(reps)])) * 1e3
+                c = float(np.mean([ev[i][2].elapsed_time(ev[i][3]) for i in range(reps)])) * 1e3
+                row[label] = {"dispatch_us": d, "combine_us": c, "frac_of_peak": 2 * nb / ((d + c) * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        finally:
+            fusco.fusco_probe_dispatch_kernel(0)
+        rows.append(row)
+        del x, eb, out, L
+    return {"reps": reps, "shapes": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -415,6 +476,9 @@ def main() -> int:
                     help="instead of the benchmark line, print dispatch and combine times for hidden sizes 2048 ... 32768")
     ap.add_argument("--token-sweep", action="store_true",
                     help="instead of the benchmark line, print plan, dispatch and combine times for 1 Ki to 64 Ki tokens")
+    ap.add_argument("--shape-sweep", action="store_true",
+                    help="instead of the benchmark line, print dispatch and combine times of other MoE shapes with "
+                         "fusco_dispatch on the token walk and on the transfer order")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -443,6 +507,9 @@ def main() -> int:
         return 0
     if args.row_sweep:
         print(json.dumps({"row_sweep": row_sweep(fusco, torch, np, W)}))
+        return 0
+    if args.shape_sweep:
+        print(json.dumps({"shape_sweep": shape_sweep(fusco, torch, np, W)}))
         return 0
     if args.plan_scaling:
         print(json.dumps({"plan_scaling": plan_scaling(fusco, torch)}))
