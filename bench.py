@@ -447,6 +447,75 @@ def shape_sweep(fusco, torch, np, W, reps=16):
     return {"reps": reps, "shapes": rows}
 
 
+def dispatch_study(fusco, torch, np, W, reps=16):
+    """The tiled dispatch over the workgroups it keeps per compute unit (fusco_probe_dispatch_occupancy), with and
+    without the pull of a tile's source rows (fusco_probe_dispatch_pull), with x in the memory-side cache and cold
+    (rotating over copies of more than 700 MB in all): the evidence for the library's choice of both.  dsv3 routing,
+    8192 tokens unless said otherwise; dispatch alternates with the combine as in a step; per-call kernel times."""
+    base = W.get_config("dsv3")
+    rows = []
+    for N, H in ((8192, 4096), (8192, 5120), (8192, 6144), (8192, 6656), (8192, 7168), (8192, 7680), (8192, 8192),
+                 (4096, 7168), (8704, 7168), (9216, 7168), (16384, 7168)):
+        cfg = base.with_tokens(N)
+        A, w = W.make_routing(cfg)
+        d_A, d_w = torch.from_numpy(A).cuda(), torch.from_numpy(w).cuda()
+        L = fusco.Layout(cfg.N, cfg.k, cfg.E, cfg.D)
+        fusco.fusco_plan(L, d_A)
+        copies = max(2, (700 << 20) // (N * H * 2) + 1)
+        xs = [torch.randn((N, H), device="cuda").to(torch.bfloat16) for _ in range(copies)]
+        eb = torch.empty((cfg.P, H), dtype=torch.bfloat16, device="cuda")
+        out = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+        row = {"N": N, "hidden": H, "row_bytes": 2 * H, "source_MiB": N * H * 2 / 2**20, "cases": []}
+        try:
+            for pull in (1, 2):
+                for rot in (1, copies):
+                    times = {}
+                    for wgs in (8, 7, 6, 5, 4):
+                        fusco.fusco_probe_dispatch_pull(pull)
+                        fusco.fusco_probe_dispatch_occupancy(wgs)
+                        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+                        for r in ev:
+                            for e in r:
+                                e.record()
+                        turn = 0
+                        for _ in range(40):
+                            fusco.fusco_dispatch(L, xs[turn % rot], eb)
+                            fusco.fusco_combine(L, eb, d_w, out)
+                            turn += 1
+                        torch.cuda.synchronize()
+                        for i in range(reps):
+                            fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
+                            fusco.fusco_dispatch(L, xs[turn % rot], eb)
+                            fusco.fusco_combine(L, eb, d_w, out)
+                            turn += 1
+                        torch.cuda.synchronize()
+                        times[str(wgs)] = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(reps)])) * 1e3
+                    row["cases"].append({"pull": pull == 2, "x": "cold" if rot > 1 else "in the memory-side cache",
+                                         "dispatch_us_by_workgroups_per_cu": times})
+            fusco.fusco_probe_dispatch_pull(0)
+            fusco.fusco_probe_dispatch_occupancy(0)
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+            for r in ev:
+                for e in r:
+                    e.record()
+            for _ in range(40):
+                fusco.fusco_dispatch(L, xs[0], eb)
+                fusco.fusco_combine(L, eb, d_w, out)
+            torch.cuda.synchronize()
+            for i in range(reps):
+                fusco.fusco_probe_time_next_call(ev[i][0], ev[i][1])
+                fusco.fusco_dispatch(L, xs[0], eb)
+                fusco.fusco_combine(L, eb, d_w, out)
+            torch.cuda.synchronize()
+            row["library_choice_us"] = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(reps)])) * 1e3
+        finally:
+            fusco.fusco_probe_dispatch_pull(0)
+            fusco.fusco_probe_dispatch_occupancy(0)
+        rows.append(row)
+        del xs, eb, out, L
+    return {"reps": reps, "k": base.k, "E": base.E, "sizes": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -479,6 +548,9 @@ def main() -> int:
     ap.add_argument("--shape-sweep", action="store_true",
                     help="instead of the benchmark line, print dispatch and combine times of other MoE shapes with "
                          "fusco_dispatch on the token walk and on the transfer order")
+    ap.add_argument("--dispatch-study", action="store_true",
+                    help="instead of the benchmark line, print the tiled dispatch's time over the workgroups per compute "
+                         "unit, with and without the pull of the source rows, with x cached and cold")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also launch the 1 GiB plain-copy probe 3 times (calibration of traffic counters)")
     args = ap.parse_args()
@@ -510,6 +582,9 @@ def main() -> int:
         return 0
     if args.shape_sweep:
         print(json.dumps({"shape_sweep": shape_sweep(fusco, torch, np, W)}))
+        return 0
+    if args.dispatch_study:
+        print(json.dumps({"dispatch_study": dispatch_study(fusco, torch, np, W)}))
         return 0
     if args.plan_scaling:
         print(json.dumps({"plan_scaling": plan_scaling(fusco, torch)}))
