@@ -97,8 +97,8 @@ int fusco_probe_dispatch_walk(int which);
 int fusco_probe_dispatch_pull(int which);
 
 /*
- * Study and test aid: how many workgroups of the tiled dispatch a compute unit holds at once.  0: automatic (the
- * library's choice for the row size).  3 ... 7: that many (the launch asks for dynamic LDS it does not use, which
+ * Study and test aid: how many workgroups of the tiled dispatch a compute unit holds at once.  0: automatic (5 to 7
+ * for whole rows of more than 8 KiB with a source tensor of at most 116 MiB, no cap otherwise).  3 ... 7: that many (the launch asks for dynamic LDS it does not use, which
  * caps the number).  8: no cap.  wgs < 0 only reads the setting.  Returns the previous setting,
  * FUSCO_ERR_INVALID_ARG for 1, 2 and values above 8.  The result of fusco_dispatch does not depend on it.
  */
