@@ -454,8 +454,8 @@ def dispatch_study(fusco, torch, np, W, reps=16):
     8192 tokens unless said otherwise; dispatch alternates with the combine as in a step; per-call kernel times."""
     base = W.get_config("dsv3")
     rows = []
-    for N, H in ((8192, 4096), (8192, 5120), (8192, 6144), (8192, 6656), (8192, 7168), (8192, 7680), (8192, 8192),
-                 (4096, 7168), (8704, 7168), (9216, 7168), (16384, 7168)):
+    for N, H in ((8192, 2560), (8192, 3072), (8192, 4096), (8192, 5120), (8192, 6144), (8192, 6656), (8192, 7168), (8192, 7680),
+                 (8192, 8192), (4096, 12288), (4096, 7168), (8704, 7168), (9216, 7168), (16384, 7168)):
         cfg = base.with_tokens(N)
         A, w = W.make_routing(cfg)
         d_A, d_w = torch.from_numpy(A).cuda(), torch.from_numpy(w).cuda()
@@ -470,7 +470,7 @@ def dispatch_study(fusco, torch, np, W, reps=16):
             for pull in (1, 2):
                 for rot in (1, copies):
                     times = {}
-                    for wgs in (8, 7, 6, 5, 4):
+                    for wgs in (16, 12, 8, 7, 6, 5, 4):
                         fusco.fusco_probe_dispatch_pull(pull)
                         fusco.fusco_probe_dispatch_occupancy(wgs)
                         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]

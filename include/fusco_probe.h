@@ -97,10 +97,11 @@ int fusco_probe_dispatch_walk(int which);
 int fusco_probe_dispatch_pull(int which);
 
 /*
- * Study and test aid: how many workgroups of the tiled dispatch a compute unit holds at once.  0: automatic (5 to 7
- * for whole rows of more than 8 KiB with a source tensor of at most 116 MiB, no cap otherwise).  3 ... 7: that many (the launch asks for dynamic LDS it does not use, which
- * caps the number).  8: no cap.  wgs < 0 only reads the setting.  Returns the previous setting,
- * FUSCO_ERR_INVALID_ARG for 1, 2 and values above 8.  The result of fusco_dispatch does not depend on it.
+ * Study and test aid: how many workgroups of the tiled dispatch a compute unit holds at once.  0: automatic (5 to
+ * 12, by the size of the rows or column segments, for rows of 4 KiB and more with a source tensor of at most
+ * 116 MiB; no cap otherwise).  3 ... 15: that many (the launch asks for dynamic LDS it does not use, which caps the
+ * number; 13 comes out as 14).  16: no cap.  wgs < 0 only reads the setting.  Returns the previous setting,
+ * FUSCO_ERR_INVALID_ARG for 1, 2 and values above 16.  The result of fusco_dispatch does not depend on it.
  */
 int fusco_probe_dispatch_occupancy(int wgs);
 

@@ -402,7 +402,7 @@ def fusco_probe_dispatch_kernel(which: int = -1) -> int:
 
 
 def fusco_probe_dispatch_occupancy(wgs: int = -1) -> int:
-    """Workgroups of the tiled dispatch per compute unit: 0 automatic, 3 ... 7 that many, 8 no cap; < 0 reads the
+    """Workgroups of the tiled dispatch per compute unit: 0 automatic, 3 ... 15 that many, 16 no cap; < 0 reads the
     setting.  Returns the previous setting."""
     rc = int(load_library().fusco_probe_dispatch_occupancy(int(wgs)))
     if rc < 0:

@@ -235,23 +235,27 @@ static std::atomic<int> g_walk_mode{0};
 // fusco_probe_dispatch_pull: 0 automatic, 1 off, 2 on
 static std::atomic<int> g_tiled_pull{0};
 
-// Dynamic LDS that lets exactly `wgs` workgroups share a compute unit's 160 KiB of LDS, which is handed out in
-// 128 blocks of 1280 bytes (3 <= wgs <= 7; the kernels have no LDS of their own); 0 for no cap.
+// Dynamic LDS that lets `wgs` workgroups share a compute unit's 160 KiB of LDS, which is handed out in 128 blocks
+// of 1280 bytes (3 <= wgs <= 15; 13 comes out as 14; the kernels have no LDS of their own); 0 for no cap.
 static size_t lds_for_occupancy(int wgs)
 {
-    if (wgs < 3 || wgs > 7) return 0;
+    if (wgs < 3 || wgs > 15) return 0;
     return (size_t)(128 / wgs) * 1280;
 }
 
 // Workgroups of the tiled dispatch per compute unit for rows (or column segments) of seg_bytes, source tensor
-// taken in one piece.  The kernel runs at the rate of its writes, which is higher the fewer rows are being
-// written at a time, as long as enough loads stay in flight: measured at 8192 tokens x 8 (dispatch alone, us,
-// source tensor in the memory-side cache, 8 / 7 / 6 / 5 / 4 workgroups): 8 KiB rows 96 / 104 / 108 / 119 / 136,
-// 9 KiB 109 / 107 / 110 / 120 / 135, 12 KiB 138 / 131 / 139 / 148 / 163, 13 KiB 151 / 150 / 146 / 149 / 164,
-// 14 KiB 165 / 164 / 162 / 157 / 171, 15 KiB 173 / 174 / 170 / 164 / 177; two segments of 8 KiB 192 / 203 / 220.
-static int tiled_workgroups_per_cu(size_t seg_bytes, int segs)
+// resident in the memory-side cache (16: no cap).  The kernel runs at the rate of its writes, which is higher the
+// fewer rows are being written at a time, as long as enough loads stay in flight: about 70-90 KiB of rows per compute
+// unit.  Measured at 8192 tokens x 8, dispatch alone, us, no cap / the cap chosen / one less: 5 KiB rows 66.6 /
+// 58.6 (12) / 58.9; 6 KiB 75.5 / 71.5 (12) / 71.7; 8 KiB 96.2 / 87.2 (12) / 87.8; 10 KiB 118.6 / 111.5 (8) / 113.8;
+// 12 KiB 140.2 / 131.9 (7) / 140.1; 13 KiB 151 / 146 (6) / 149; 14 KiB 165 / 157 (5) / 171; 15 KiB 173 / 164 (5) / 177;
+// two segments of 8 KiB 192.1 / 189.3 (12); of 12 KiB (4096 tokens) 142.2 / 135.1 (7).  Rows shorter than 4 KiB
+// are moved by workgroups of one or two waves, of which a compute unit should hold more than a cap allows.
+static int tiled_workgroups_per_cu(size_t seg_bytes)
 {
-    if (segs > 1 || seg_bytes <= 8192) return 8;
+    if (seg_bytes < 4096) return 16;
+    if (seg_bytes <= 8192) return 12;
+    if (seg_bytes <= 10240) return 8;
     if (seg_bytes <= 12288) return 7;
     if (seg_bytes <= 13312) return 6;
     return 5;
@@ -395,7 +399,7 @@ int fusco_dispatch(const fusco_layout *L, const void *d_x, size_t row_bytes, con
         const int pull_knob = g_tiled_pull.load(std::memory_order_relaxed);
         const bool pull = pull_knob == 0 ? !chunked : pull_knob == 2;
         const int wgs = occ_knob > 0 ? occ_knob
-                        : (source_bytes <= kResidentSourceBytes ? tiled_workgroups_per_cu((size_t)per * 16, segs) : 8);
+                        : (source_bytes <= kResidentSourceBytes ? tiled_workgroups_per_cu((size_t)per * 16) : 16);
         const size_t lds = lds_for_occupancy(wgs);
         for (size_t tile0 = 0; tile0 < (size_t)L->tile_count; tile0 += chunk_tiles) {
             const size_t tiles_here = std::min(chunk_tiles, (size_t)L->tile_count - tile0);
@@ -765,7 +769,7 @@ int fusco_probe_dispatch_pull(int which)
 
 int fusco_probe_dispatch_occupancy(int wgs)
 {
-    if (wgs > 8 || (wgs > 0 && wgs < 3)) return FUSCO_ERR_INVALID_ARG;
+    if (wgs > 16 || (wgs > 0 && wgs < 3)) return FUSCO_ERR_INVALID_ARG;   // 16: no cap
     return wgs < 0 ? g_tiled_occupancy.load() : g_tiled_occupancy.exchange(wgs);
 }
 

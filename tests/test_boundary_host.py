@@ -242,9 +242,9 @@ def test_entry_points_reject_bad_arguments_without_launching(lib):
     assert lib.fusco_probe_dispatch_kernel(2) == 0 and lib.fusco_probe_dispatch_kernel(0) == 2
     assert lib.fusco_probe_dispatch_kernel(3) == -1 and lib.fusco_probe_dispatch_kernel(-1) == 0
     assert lib.fusco_probe_dispatch_occupancy(-1) == 0 and lib.fusco_probe_dispatch_occupancy(5) == 0
-    assert lib.fusco_probe_dispatch_occupancy(-1) == 5 and lib.fusco_probe_dispatch_occupancy(8) == 5
-    assert lib.fusco_probe_dispatch_occupancy(2) == -1 and lib.fusco_probe_dispatch_occupancy(9) == -1     # 1, 2 and > 8 refused
-    assert lib.fusco_probe_dispatch_occupancy(0) == 8 and lib.fusco_probe_dispatch_occupancy(-1) == 0
+    assert lib.fusco_probe_dispatch_occupancy(-1) == 5 and lib.fusco_probe_dispatch_occupancy(16) == 5
+    assert lib.fusco_probe_dispatch_occupancy(2) == -1 and lib.fusco_probe_dispatch_occupancy(17) == -1    # 1, 2 and > 16 refused
+    assert lib.fusco_probe_dispatch_occupancy(0) == 16 and lib.fusco_probe_dispatch_occupancy(-1) == 0
     assert lib.fusco_probe_dispatch_walk(-1) == 0 and lib.fusco_probe_dispatch_walk(4) == 0
     assert lib.fusco_probe_dispatch_walk(5) == -1 and lib.fusco_probe_dispatch_walk(0) == 4 and lib.fusco_probe_dispatch_walk(-1) == 0
     assert lib.fusco_probe_dispatch_pull(-1) == 0 and lib.fusco_probe_dispatch_pull(2) == 0

@@ -743,7 +743,7 @@ def test_tiled_dispatch_study_knobs_do_not_change_the_result(fusco, oracle, tran
         _, expert_want = oracle.dispatch(want, x)
     assert fusco.fusco_probe_dispatch_occupancy() == 0 and fusco.fusco_probe_dispatch_pull() == 0
     try:
-        for occupancy in (3, 5, 7, 8):
+        for occupancy in (3, 5, 7, 12, 16):
             for pull in (1, 2):
                 fusco.fusco_probe_dispatch_occupancy(occupancy)
                 fusco.fusco_probe_dispatch_pull(pull)
